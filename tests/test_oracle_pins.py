@@ -1,0 +1,373 @@
+"""Pins for the CPU oracle: every function is checked against something other than
+itself - a value the paper prints, a closed form, a special case that reduces to a
+library routine, or brute force on tiny inputs."""
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+
+from oracle import draft_attention as oa
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rng(seed=0):
+    return np.random.default_rng(seed)
+
+
+# ---------------------------------------------------------------- sizes
+def test_config_dims_table():
+    for line in open(os.path.join(GOLDEN, "config_dims.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        left, right = line.split(":")
+        name, T, fh, fw, s = left.split()
+        gh, gw, g, n, n_pad, k = (int(v) for v in right.split())
+        dims = oa.derive_dims(int(T), int(fh), int(fw), 8, 8, float(s))
+        assert (dims["gh"], dims["gw"], dims["g"], dims["n"], dims["n_pad"], dims["k"]) == \
+            (gh, gw, g, n, n_pad, k), name
+
+
+def test_k_rule_edges():
+    assert oa.derive_dims(1, 8, 8, 8, 8, 0.0)["k"] == 1
+    assert oa.derive_dims(4, 16, 16, 8, 8, 0.0)["k"] == 16            # nothing dropped
+    assert oa.derive_dims(4, 16, 16, 8, 8, 0.999)["k"] == 1           # clamped to >= 1
+    assert oa.derive_dims(4, 16, 16, 8, 8, 0.5, keep_blocks=3)["k"] == 3
+    assert oa.derive_dims(4, 16, 16, 8, 8, 0.5, keep_blocks=99)["k"] == 16
+    # (1 - 0.9) * 1980 is 197.99999999999994 in doubles; the rule must still give 198
+    assert oa.derive_dims(33, 45, 80, 8, 8, 0.9)["k"] == 198
+
+
+# ---------------------------------------------------------------- Algorithm 1 / 2
+def test_reorder_fig3_toy():
+    for line in open(os.path.join(GOLDEN, "fig3_reorder_toy.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        left, right = line.split(":")
+        fw, ph, pw = (int(v) for v in left.split())
+        first_block = [int(v) - 1 for v in right.split()]
+        for fh in (2, 4, 6):
+            perm, valid = oa.reorder_index(1, fh, fw, ph, pw)
+            assert list(perm[:ph * pw]) == first_block
+            assert (valid == ph * pw).all()
+
+
+def test_reorder_matches_textbook_patchify_when_divisible():
+    for (T, fh, fw, ph, pw) in [(3, 16, 24, 8, 8), (2, 32, 48, 8, 16), (1, 4, 4, 2, 2), (2, 6, 9, 3, 3)]:
+        perm, valid = oa.reorder_index(T, fh, fw, ph, pw)
+        ref = (np.arange(T * fh * fw).reshape(T, fh // ph, ph, fw // pw, pw)
+               .transpose(0, 1, 3, 2, 4).reshape(-1))
+        assert np.array_equal(perm, ref)
+        assert (valid == ph * pw).all()
+
+
+@pytest.mark.parametrize("shape", [(2, 30, 52, 8, 8), (3, 45, 80, 8, 8), (2, 5, 7, 2, 3), (1, 9, 9, 8, 8)])
+def test_reorder_padding_properties(shape):
+    T, fh, fw, ph, pw = shape
+    perm, valid = oa.reorder_index(T, fh, fw, ph, pw)
+    dims = oa.derive_dims(*shape)
+    n, block, g = dims["n"], dims["block"], dims["g"]
+    assert len(perm) == dims["n_pad"] and len(valid) == g
+    assert valid.sum() == n
+    real = perm[perm >= 0]
+    assert np.array_equal(np.sort(real), np.arange(n))            # bijection onto the real slots
+    pm = perm.reshape(g, block)
+    for i in range(g):                                            # valid first, pads at the tail
+        assert (pm[i, :valid[i]] >= 0).all() and (pm[i, valid[i]:] == -1).all()
+        # every token of a block lies in one frame and inside one ph x pw window
+        tok = pm[i, :valid[i]]
+        t, rem = tok // (fh * fw), tok % (fh * fw)
+        y, x = rem // fw, rem % fw
+        assert len(set(t)) == 1 and len(set(y // ph)) == 1 and len(set(x // pw)) == 1
+        assert (np.diff(tok) > 0).all()                           # raster order inside the block
+    # block order is (frame, patch row, patch column)
+    first = pm[:, 0]
+    assert (np.diff(first // (fh * fw)) >= 0).all()
+
+
+def test_valid_counts_of_benchmark_shapes():
+    _, valid = oa.reorder_index(1, 45, 80, 8, 8)
+    assert sorted(set(valid)) == [40, 64]
+    _, valid = oa.reorder_index(1, 30, 52, 8, 8)
+    assert sorted(set(valid)) == [24, 32, 48, 64]
+
+
+def test_reorder_identity_when_window_spans_the_row():
+    perm, _ = oa.reorder_index(2, 8, 5, 4, 5)
+    assert np.array_equal(perm, np.arange(2 * 8 * 5))
+
+
+def test_restore_is_the_inverse():
+    for shape in [(2, 30, 52, 8, 8), (1, 4, 4, 2, 2), (2, 5, 7, 2, 3)]:
+        perm, _ = oa.reorder_index(*shape)
+        n = shape[0] * shape[1] * shape[2]
+        inv = oa.restore_index(perm, n)
+        assert np.array_equal(perm[inv], np.arange(n))
+        X = _rng(1).normal(size=(n, 3))
+        Xp = oa.permute(X, perm)
+        assert np.array_equal(oa.restore(Xp, inv), X)              # restore(permute) = identity
+        assert (Xp[perm < 0] == 0).all()                           # pad rows are zeros
+        # restore_index agrees with a direct argsort of the real slots
+        slots = np.nonzero(perm >= 0)[0]
+        assert np.array_equal(inv, slots[np.argsort(perm[slots])])
+
+
+# ---------------------------------------------------------------- pooling
+def test_pool_hand_example_partial_patches():
+    # 3x3 frame, 2x2 window, value = token index: means worked by hand
+    perm, valid = oa.reorder_index(1, 3, 3, 2, 2)
+    X = np.arange(9, dtype=np.float64)[:, None]
+    assert list(valid) == [4, 2, 2, 1]
+    assert np.allclose(oa.pool_f64(X, perm, valid, 4)[:, 0], [2.0, 3.5, 6.5, 8.0])
+    assert np.array_equal(oa.pool_canonical_f32(X.astype(np.float32), perm, valid, 4)[:, 0],
+                          np.float32([2.0, 3.5, 6.5, 8.0]))
+
+
+def test_pool_window_1x1_is_identity_and_constant_field():
+    X = _rng(2).normal(size=(2 * 3 * 5, 4))
+    perm, valid = oa.reorder_index(2, 3, 5, 1, 1)
+    assert np.array_equal(oa.pool_f64(X, perm, valid, 1), X)
+    assert np.array_equal(oa.pool_canonical_f32(X.astype(np.float32), perm, valid, 1), X.astype(np.float32))
+    perm, valid = oa.reorder_index(2, 11, 13, 8, 8)
+    C = np.full((2 * 11 * 13, 3), 1.25)
+    assert np.allclose(oa.pool_f64(C, perm, valid, 64), 1.25, rtol=0, atol=1e-15)
+    assert np.array_equal(oa.pool_canonical_f32(C.astype(np.float32), perm, valid, 64),
+                          np.full((len(valid), 3), 1.25, np.float32))       # sums of 1.25 are exact
+
+
+def test_pool_matches_strided_average_pool_when_divisible():
+    T, fh, fw, ph, pw, d = 2, 16, 24, 8, 8, 5
+    X = _rng(3).normal(size=(T * fh * fw, d))
+    perm, valid = oa.reorder_index(T, fh, fw, ph, pw)
+    ref = X.reshape(T, fh // ph, ph, fw // pw, pw, d).mean(axis=(2, 4)).reshape(-1, d)
+    got = oa.pool_f64(X, perm, valid, ph * pw)
+    assert np.allclose(got, ref, rtol=1e-13, atol=1e-13)
+    got32 = oa.pool_canonical_f32(X.astype(np.float32), perm, valid, ph * pw)
+    assert np.allclose(got32, ref, rtol=2e-6, atol=2e-6)
+
+
+def test_pool_canonical_order_is_sequential_float32():
+    # values chosen so that float32 summation order matters: sequential slot order gives a
+    # different answer from pairwise; the oracle must give the sequential one
+    perm, valid = oa.reorder_index(1, 2, 2, 2, 2)
+    x = np.float32([1e8, 1.0, -1e8, 1.0])[:, None]
+    seq = np.float32(0)
+    for v in x[:, 0]:
+        seq = np.float32(seq + v)
+    assert seq == np.float32(1.0)
+    got = oa.pool_canonical_f32(x, perm, valid, 4)[0, 0]
+    assert got == np.float32(seq / np.float32(4.0))
+
+
+# ---------------------------------------------------------------- draft map
+def test_draft_logits_planted():
+    # one non-zero channel: logit_ij = a_i * b_j / sqrt(d); asymmetric so a transposed operand fails
+    d = 16
+    a = np.array([1.0, 2.0, -3.0])
+    b = np.array([0.5, 4.0])
+    qp = np.zeros((3, d)); qp[:, 2] = a
+    kp = np.zeros((2, d)); kp[:, 2] = b
+    ref = np.outer(a, b) / 4.0
+    assert np.allclose(oa.draft_logits_f64(qp, kp), ref)
+    assert np.array_equal(oa.draft_logits_canonical_f32(qp.astype(np.float32), kp.astype(np.float32)),
+                          ref.astype(np.float32))
+
+
+def test_draft_logits_canonical_close_to_f64_and_not_fused():
+    r = _rng(4)
+    qp = r.normal(size=(40, 128)).astype(np.float32)
+    kp = r.normal(size=(50, 128)).astype(np.float32)
+    L32 = oa.draft_logits_canonical_f32(qp, kp)
+    L64 = oa.draft_logits_f64(qp.astype(np.float64), kp.astype(np.float64))
+    assert np.abs(L32 - L64).max() < 2e-5
+    # scalar re-evaluation of the stated order for a few entries
+    scale = np.float32(1.0 / math.sqrt(128))
+    assert scale.view(np.uint32) == 0x3DB504F3
+    for (i, j) in [(0, 0), (7, 31), (39, 49)]:
+        acc = np.float32(0)
+        for c in range(128):
+            acc = np.float32(acc + np.float32(qp[i, c] * kp[j, c]))
+        assert L32[i, j] == np.float32(acc * scale)
+
+
+def test_draft_map_rows_sum_to_one_and_uniform_case():
+    r = _rng(5)
+    qp, kp = r.normal(size=(30, 16)) * 3, r.normal(size=(30, 16)) * 3
+    A = oa.draft_map(qp, kp)
+    assert np.allclose(A.sum(axis=1), 1.0, atol=1e-13) and (A >= 0).all()
+    same = np.tile(r.normal(size=(1, 16)), (12, 1))
+    assert np.allclose(oa.draft_map(same, same), 1.0 / 12, atol=1e-14)
+
+
+def test_draft_map_window_1x1_equals_token_level_map():
+    T, fh, fw, d = 2, 3, 4, 8
+    r = _rng(6)
+    Q, K = r.normal(size=(T * fh * fw, d)), r.normal(size=(T * fh * fw, d))
+    perm, valid = oa.reorder_index(T, fh, fw, 1, 1)
+    A = oa.draft_map(oa.pool_f64(Q, perm, valid, 1), oa.pool_f64(K, perm, valid, 1))
+    ref = scipy.special.softmax(Q @ K.T / math.sqrt(d), axis=1)
+    assert np.allclose(A, ref, atol=1e-14)
+
+
+def test_theorem1_bound_on_tiny_input():
+    # ||S - S_draft||_F <= delta * n with equal region sizes (Theorem 1; logits unscaled as there)
+    T, fh, fw, ph, pw, d = 2, 4, 4, 2, 2, 6
+    r = _rng(7)
+    Q, K = r.normal(size=(T * fh * fw, d)), r.normal(size=(T * fh * fw, d))
+    perm, valid = oa.reorder_index(T, fh, fw, ph, pw)
+    n, g, block = T * fh * fw, len(valid), ph * pw
+    S = Q @ K.T
+    St = oa.pool_f64(Q, perm, valid, block) @ oa.pool_f64(K, perm, valid, block).T
+    region = np.empty(n, dtype=int)
+    region[perm] = np.repeat(np.arange(g), block)
+    Sd = St[np.ix_(region, region)]
+    delta = np.abs(S - Sd).max()
+    assert np.linalg.norm(S - Sd) <= delta * n + 1e-12
+    # block means of S equal the pooled logits (bilinearity): pins pooling + logits together
+    for i in range(g):
+        for j in range(g):
+            assert abs(S[np.ix_(region == i, region == j)].mean() - St[i, j]) < 1e-12
+
+
+# ---------------------------------------------------------------- selection
+def _brute_select(row, k):
+    order = sorted(range(len(row)), key=lambda j: (-float(row[j]), j))[:k]
+    return sorted(order)
+
+
+def test_select_brute_force_random_and_duplicates():
+    r = _rng(8)
+    for trial in range(6):
+        g = int(r.integers(3, 90))
+        k = int(r.integers(1, g + 1))
+        L = r.normal(size=(g, g)).astype(np.float32)
+        if trial % 2:
+            L = np.round(L * 2) / 2                                  # many exact duplicates
+        idx, mask = oa.select_blocks(L, k)
+        for i in range(g):
+            assert list(idx[i]) == _brute_select(L[i], k)
+        assert (mask.sum(axis=1) == k).all()
+        assert all(mask[i, idx[i]].all() for i in range(g))
+
+
+def test_select_special_cases():
+    L = np.zeros((5, 9), np.float32)
+    idx, _ = oa.select_blocks(L, 4)
+    assert (idx == np.arange(4)).all()                               # all equal -> lowest columns
+    row = np.float32([[3, 9, 1, 9, 7, -2, 9]])
+    assert list(oa.select_blocks(row, 1)[0][0]) == [1]               # argmax, lowest index
+    assert list(oa.select_blocks(row, 2)[0][0]) == [1, 3]
+    assert list(oa.select_blocks(row, 4)[0][0]) == [1, 3, 4, 6]
+    assert list(oa.select_blocks(row, 7)[0][0]) == list(range(7))    # k = g keeps everything
+    z = np.float32([[0.0, -0.0, 0.0, -1.0]])
+    assert list(oa.select_blocks(z, 2)[0][0]) == [0, 1]              # -0.0 ties with +0.0
+
+
+def test_select_order_equals_order_of_softmax_when_distinct():
+    r = _rng(9)
+    L = r.normal(size=(20, 20))
+    A = oa.softmax_rows(L)
+    assert np.array_equal(oa.select_blocks(L, 7)[0], oa.select_blocks(A, 7)[0])
+
+
+# ---------------------------------------------------------------- attention
+def _full_attention_loops(Q, K, V):
+    n, d = Q.shape
+    O = np.zeros_like(V)
+    for u in range(n):
+        s = [sum(Q[u, c] * K[v, c] for c in range(d)) / math.sqrt(d) for v in range(n)]
+        m = max(s)
+        e = [math.exp(x - m) for x in s]
+        z = sum(e)
+        for v in range(n):
+            O[u] += (e[v] / z) * V[v]
+    return O
+
+
+def test_full_attention_against_loops_and_scipy():
+    r = _rng(10)
+    Q, K, V = (r.normal(size=(12, 4)) for _ in range(3))
+    O = oa.full_attention(Q, K, V)
+    assert np.allclose(O, _full_attention_loops(Q, K, V), atol=1e-13)
+    assert np.allclose(O, scipy.special.softmax(Q @ K.T / 2.0, axis=1) @ V, atol=1e-13)
+
+
+def _tiny_problem(seed, T=2, fh=5, fw=6, ph=2, pw=4, d=8, scale=1.0):
+    r = _rng(seed)
+    n = T * fh * fw
+    Q, K, V = r.normal(size=(n, d)) * scale, r.normal(size=(n, d)) * scale, r.normal(size=(n, d))
+    perm, valid = oa.reorder_index(T, fh, fw, ph, pw)
+    inv = oa.restore_index(perm, n)
+    return Q, K, V, perm, valid, inv, ph * pw, n
+
+
+def test_zero_sparsity_equals_full_attention():
+    Q, K, V, perm, valid, inv, block, n = _tiny_problem(11)
+    g = len(valid)
+    idx = np.tile(np.arange(g), (g, 1))
+    Op = oa.sparse_attention_blocks(oa.permute(Q, perm), oa.permute(K, perm), oa.permute(V, perm),
+                                    idx, valid, block)
+    assert np.allclose(oa.restore(Op, inv), _full_attention_loops(Q, K, V), atol=1e-12)
+
+
+def test_block_form_equals_dense_masked_form():
+    Q, K, V, perm, valid, inv, block, n = _tiny_problem(12, scale=2.0)
+    g = len(valid)
+    qp = oa.pool_canonical_f32(Q.astype(np.float32), perm, valid, block)
+    kp = oa.pool_canonical_f32(K.astype(np.float32), perm, valid, block)
+    idx, mask = oa.select_blocks(oa.draft_logits_canonical_f32(qp, kp), max(1, g // 3))
+    Op, lse = oa.sparse_attention_blocks(oa.permute(Q, perm), oa.permute(K, perm), oa.permute(V, perm),
+                                         idx, valid, block, want_lse=True)
+    Mhat = oa.lift_mask(mask, perm, valid, block, n)
+    assert Mhat.shape == (n, n) and Mhat.sum() == sum(valid[i] * valid[idx[i]].sum() for i in range(g))
+    dense = oa.sparse_attention_dense(Q, K, V, Mhat)
+    assert np.allclose(oa.restore(Op, inv), dense, atol=1e-12)
+    # the LSE is that of the kept logits
+    S = np.where(Mhat.astype(bool), Q @ K.T / math.sqrt(Q.shape[1]), -np.inf)
+    assert np.allclose(oa.restore(lse, inv), scipy.special.logsumexp(S, axis=1), atol=1e-12)
+    # pad query slots stay zero
+    assert (Op[perm < 0] == 0).all()
+
+
+def test_attention_closed_forms():
+    Q, K, V, perm, valid, inv, block, n = _tiny_problem(13)
+    g = len(valid)
+    r = _rng(14)
+    idx = np.sort(np.stack([r.choice(g, 3, replace=False) for _ in range(g)]), axis=1)
+    Qp, Kp, Vp = oa.permute(Q, perm), oa.permute(K, perm), oa.permute(V, perm)
+    # V constant -> O constant (on real slots)
+    Vc = np.where((perm >= 0)[:, None], 0.75, 0.0) * np.ones_like(Vp)
+    Oc = oa.sparse_attention_blocks(Qp, Kp, Vc, idx, valid, block)
+    assert np.allclose(Oc[perm >= 0], 0.75, atol=1e-14)
+    # all queries and keys equal -> O = mean of V over the kept valid keys (pad keys excluded)
+    same = np.where((perm >= 0)[:, None], 1.0, 0.0) * np.ones_like(Qp) * 0.3
+    Om = oa.sparse_attention_blocks(same, same, Vp, idx, valid, block)
+    for i in range(g):
+        keys = np.concatenate([np.arange(j * block, j * block + valid[j]) for j in idx[i]])
+        assert np.allclose(Om[i * block:i * block + valid[i]], Vp[keys].mean(axis=0), atol=1e-13)
+    # the order of the kept key blocks does not matter
+    O1 = oa.sparse_attention_blocks(Qp, Kp, Vp, idx, valid, block)
+    O2 = oa.sparse_attention_blocks(Qp, Kp, Vp, idx[:, ::-1], valid, block)
+    assert np.allclose(O1, O2, atol=1e-13)
+    # rows= restricts the work and leaves the rest zero
+    O3 = oa.sparse_attention_blocks(Qp, Kp, Vp, idx, valid, block, rows=[1, 4])
+    assert np.array_equal(O3[block:2 * block], O1[block:2 * block]) and (O3[:block] == 0).all()
+
+
+def test_forward_head_chain_on_tiny_config_and_bf16_widening():
+    from paper_2505_14708_amd import workloads as W
+    w = W.CONFIGS["tiny_fp32"]
+    q, k, v = W.make_head(w, 0, 0)
+    out = oa.forward_head(q, k, v, w.dtype, w.T, w.fh, w.fw, w.ph, w.pw, w.sparsity)
+    assert out["dims"]["k"] == 4 and out["idx"].shape == (8, 4)
+    assert out["O"].shape == (512, 64)
+    # the restored output equals the dense masked form on the original order
+    Mhat = oa.lift_mask(out["mask"], out["perm"], out["valid"], 64, 512)
+    dense = oa.sparse_attention_dense(*(x.astype(np.float64) for x in (q, k, v)), Mhat)
+    assert np.allclose(out["O"], dense, atol=1e-12)
+    # bf16 widening is exact and matches the generator's own helper
+    bits = np.uint16([0x3F80, 0xC049, 0x0000, 0x8000, 0x7F7F])
+    assert np.array_equal(oa.widen_f32(bits, oa.BF16), W.bf16_bits_to_f32(bits))
+    assert list(oa.widen_f64(bits, oa.BF16)[:2]) == [1.0, -3.140625]
