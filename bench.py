@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the DraftAttention hot path on one MI355X.
+
+A step is one da_forward over one batch of synthetic Q, K, V (pool -> draft logits ->
+top-k -> reorder -> block-sparse attention -> restore), inputs resident in HBM.  The
+workload is the headline configuration: 118 800 tokens (33 latent frames of 45x80), 24
+heads of 128, 8x8 pooling, 90 % sparsity, bf16.  Prints ONE JSON line.
+
+  value        effective TFLOP/s of the whole step: 4*N*N*d*H*(k/g) / step time
+  ms_per_step  milliseconds per layer (the other half of the metric)
+  roofline     the block-sparse attention kernel against the bf16 MFMA peak; its launch
+               duration is measured with HIP events on the launch stream in a second loop
+               that issues the same kernels stage by stage through the C ABI
+  cpu_baseline the NumPy float64 oracle timed on this host on a bounded sample
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from paper_2505_14708_amd import workloads as W  # noqa: E402
+
+METRIC = "sparse-attn ms/layer + effective MFMA TFLOP/s @118.8k tokens, 90% sparsity"
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def cpu_baseline(w, Q, K, V, budget_s=20.0):
+    """Time the oracle (as it stands) on head 0: pooling, draft logits, selection and the
+    reordering in full, the attention on as many evenly spaced query blocks as fit the
+    budget; extrapolate to one layer."""
+    from oracle import draft_attention as oa
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    q, k, v = Q[0, 0], K[0, 0], V[0, 0]
+    t0 = time.perf_counter()
+    dims = oa.derive_dims(w.T, w.fh, w.fw, w.ph, w.pw, w.sparsity)
+    perm, valid = oa.reorder_index(w.T, w.fh, w.fw, w.ph, w.pw)
+    inv = oa.restore_index(perm, dims["n"])
+    qp = oa.pool_canonical_f32(oa.widen_f32(q, w.dtype), perm, valid, dims["block"])
+    kp = oa.pool_canonical_f32(oa.widen_f32(k, w.dtype), perm, valid, dims["block"])
+    idx, _ = oa.select_blocks(oa.draft_logits_canonical_f32(qp, kp), dims["k"])
+    Qp, Kp, Vp = (oa.permute(oa.widen_f64(x, w.dtype), perm) for x in (q, k, v))
+    t_fixed = time.perf_counter() - t0
+    g = dims["g"]
+    done, t_attn = 0, 0.0
+    Op = None
+    order = np.linspace(0, g - 1, num=min(g, 512)).astype(int)
+    while done < len(order) and t_attn < max(2.0, budget_s - t_fixed):
+        rows = order[done:done + 8]
+        t1 = time.perf_counter()
+        Op = oa.sparse_attention_blocks(Qp, Kp, Vp, idx, valid, dims["block"], rows=rows)
+        t_attn += time.perf_counter() - t1
+        done += len(rows)
+    t1 = time.perf_counter()
+    oa.restore(Op, inv)
+    t_fixed += time.perf_counter() - t1
+    per_head = t_fixed + t_attn * g / done
+    layer_s = per_head * w.B * w.H
+    eff_flop = 4.0 * w.N * w.N * w.d * w.B * w.H * dims["k"] / g
+    return {"value": eff_flop / layer_s / 1e12, "unit": "TFLOP/s effective", "cores": int(threads),
+            "kind": "oracle", "ms_per_layer_extrapolated": layer_s * 1e3,
+            "sample": (f"head 0 of {w.H}: pool+draft+top-k+reorder+restore in full ({t_fixed:.1f} s), attention on "
+                       f"{done} of {g} query blocks ({t_attn:.1f} s); extrapolated to {w.B * w.H} heads")}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="720p_hunyuan", choices=list(W.CONFIGS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the path is independent per head and would shard "
+              "by heads with no collectives); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    w = W.CONFIGS[args.config]
+    t0 = time.time()
+    Q, K, V = W.make_qkv(w, threads=8)
+    print(f"[bench] inputs for {w.name} generated in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
+
+    import torch
+    from paper_2505_14708_amd import binding as da
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    tdt = torch.float32 if w.dtype == W.F32 else torch.bfloat16
+
+    def dev(x):
+        if w.dtype == W.F32:
+            return torch.from_numpy(x).cuda()
+        return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+
+    p = da.problem_of(w)
+    dims = da.da_derive(p)
+    dQ, dK, dV = dev(Q), dev(K), dev(V)
+    O = torch.empty((w.B, w.H, dims.n, w.d), dtype=tdt, device="cuda")
+    ws = torch.empty(da.da_workspace_size(p), dtype=torch.uint8, device="cuda")
+    g, k = dims.g, dims.k
+    eff_flop = 4.0 * w.N * w.N * w.d * w.B * w.H * k / g
+
+    # ---- the timed region: K steps of the whole path
+    for _ in range(args.warmup):
+        da.da_forward(p, dQ, dK, dV, O, ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        da.da_forward(p, dQ, dK, dV, O, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_step = e0.elapsed_time(e1) / args.steps
+
+    # ---- the same launches stage by stage, HIP events (torch's current stream is the launch stream)
+    es = torch.float32 if w.dtype == W.F32 else torch.bfloat16
+    Qp = torch.empty((w.B, w.H, dims.n_pad, w.d), dtype=es, device="cuda")
+    Kp, Op = torch.empty_like(Qp), torch.empty_like(Qp)
+    Vt = torch.empty((w.B, w.H, g, w.d, dims.block), dtype=es, device="cuda")
+    q_pool = torch.empty((w.B, w.H, g, w.d), dtype=torch.float32, device="cuda")
+    k_pool = torch.empty_like(q_pool)
+    logits = torch.empty((w.B, w.H, g, g), dtype=torch.float32, device="cuda")
+    idx = torch.empty((w.B, w.H, g, k), dtype=torch.int32, device="cuda")
+    stages = [
+        ("pool+draft_logits", lambda: da.da_draft_map(p, dQ, dK, q_pool, k_pool, logits, None)),
+        ("select", lambda: da.da_select_blocks(p, logits, idx, None)),
+        ("reorder_qkv", lambda: (da.da_permute(p, dQ, Qp, da.DA_REORDER_ROWS), da.da_permute(p, dK, Kp, da.DA_REORDER_ROWS),
+                                 da.da_permute(p, dV, Vt, da.DA_REORDER_VT))),
+        ("sparse_attn", lambda: da.da_sparse_attn(p, Qp, Kp, Vt, idx, Op, None)),
+        ("restore", lambda: da.da_permute(p, Op, O, da.DA_RESTORE)),
+    ]
+    acc = {name: 0.0 for name, _ in stages}
+    for it in range(args.warmup + args.steps):
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)]
+        evs[0].record()
+        for i, (_, fn) in enumerate(stages):
+            fn()
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        if it >= args.warmup:
+            for i, (name, _) in enumerate(stages):
+                acc[name] += evs[i].elapsed_time(evs[i + 1])
+    stage_ms = {name: v / args.steps for name, v in acc.items()}
+    attn_ms = stage_ms["sparse_attn"]
+    esz = 4 if w.dtype == W.F32 else 2
+    reorder_bytes = 3.0 * (dims.n + dims.n_pad) * w.d * esz * w.B * w.H
+    restore_bytes = 1.0 * (dims.n + dims.n_pad) * w.d * esz * w.B * w.H
+
+    out = {
+        "metric": METRIC,
+        "value": eff_flop / (ms_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s effective (whole step)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if w.dtype == W.F32 else "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "d": w.d, "T": w.T, "frame": [w.fh, w.fw], "N": w.N,
+                   "pool": [w.ph, w.pw], "sparsity": w.sparsity, "g": g, "k": k, "n_pad": int(dims.n_pad)},
+        "roofline": {"kernel": "attn_bf16_kernel (da_sparse_attn)", "bound": "mfma",
+                     "achieved": eff_flop / (attn_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": eff_flop / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, "traffic": None,
+                     "launch_ms": attn_ms, "flop_per_launch": eff_flop},
+        "stages_ms": stage_ms,
+        "hbm_stages": {"reorder_qkv_GBs": reorder_bytes / (stage_ms["reorder_qkv"] * 1e-3) / 1e9,
+                       "restore_GBs": restore_bytes / (stage_ms["restore"] * 1e-3) / 1e9, "peak_GBs": PEAK_HBM_GBS},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, Q, K, V)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

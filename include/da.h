@@ -1,0 +1,156 @@
+/*
+ * da.h - C ABI of the MI355X (gfx950) DraftAttention hot path.
+ *
+ * The path replaces full 3D attention in one attention module of a video diffusion
+ * transformer (paper: arxiv 2505.14708, Section 3).  Per (batch, head):
+ *
+ *   pool Q,K inside each latent frame      Definition 3.2 (average pooling equations)
+ *   draft map  softmax(Q~ K~^T / sqrt(d))  Definition 3.2 (draft attention map equation)
+ *   keep the top k key blocks per row      "Guided Sparsity via Draft Attention"
+ *   reorder Q,K,V so a patch is a block    Algorithm 1, Section 3.3 "Execution"
+ *   block-sparse attention                 SparseAttn equation, Section 3.1
+ *   restore the order of O                 Algorithm 2, Section 3.3 "Restoration"
+ *
+ * Conventions common to every call
+ *   - Tensors Q, K, V, O are [B, H, N, d], d fastest, contiguous, N = T*fh*fw and the token
+ *     index is n = t*fh*fw + y*fw + x (the idx of Algorithm 1).  dtype DA_BF16 stores
+ *     bfloat16, DA_F32 stores float.
+ *   - A frame is cut into gh x gw = ceil(fh/ph) x ceil(fw/pw) patches anchored at (0,0);
+ *     g = T*gh*gw blocks in (frame, patch row, patch column) order; block = ph*pw slots;
+ *     n_pad = g*block.  A block holds its valid tokens in (row, column) raster order
+ *     first and pad slots at its tail (Section 4.1 only says "appropriate padding").
+ *   - Unless a parameter says "host", every pointer is a DEVICE pointer owned by the
+ *     caller; the library neither allocates, frees nor keeps it.  Device pointers must be
+ *     16-byte aligned.  Outputs must not alias inputs.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work: no synchronisation, no host read-back, no allocation.
+ *   - Return value: DA_OK (0) or a negative da_status.  On error nothing was launched,
+ *     except DA_ERR_HIP, which reports a failed launch.  No global mutable state; calls
+ *     on different streams may run concurrently if their buffers are disjoint.
+ *   - NaN/Inf in the inputs give unspecified values but never a fault.
+ */
+#ifndef DA_H
+#define DA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { DA_F32 = 0, DA_BF16 = 1 };
+
+typedef enum da_status {
+  DA_OK = 0,
+  DA_ERR_NULL = -1,        /* a required pointer is NULL */
+  DA_ERR_DIM = -2,         /* a size is not positive, a ratio is outside [0,1), or a product overflows */
+  DA_ERR_UNSUPPORTED = -3, /* valid, but no kernel: see da_sparse_attn */
+  DA_ERR_WORKSPACE = -4,   /* ws_bytes is smaller than da_workspace_size() */
+  DA_ERR_ALIGN = -5,       /* a device pointer is not 16-byte aligned */
+  DA_ERR_HIP = -6          /* the HIP runtime refused a launch */
+} da_status;
+
+/* The problem statement of Definitions 3.1/3.2 and the inputs of Algorithm 1 (host struct). */
+typedef struct da_problem {
+  int32_t B, H;        /* batch, heads */
+  int32_t T, fh, fw;   /* latent frames, frame height and width in tokens: Algorithm 1's F, H, W */
+  int32_t d;           /* head dimension */
+  int32_t ph, pw;      /* pooling window == stride: Algorithm 1's h, w */
+  int32_t dtype;       /* DA_F32 or DA_BF16: storage type of Q, K, V, O and their reordered copies */
+  int32_t keep_blocks; /* > 0: k given explicitly (clamped to g), `sparsity` ignored; 0: use `sparsity` */
+  double  sparsity;    /* fraction of key blocks dropped per query block, in [0,1); the paper's r = 1 - sparsity */
+} da_problem;
+
+typedef struct da_dims {
+  int32_t gh, gw;      /* patches per frame along y and x */
+  int32_t g;           /* blocks (regions R_i of Definition 3.2) per head */
+  int32_t block;       /* slots per block, ph*pw */
+  int32_t k;           /* key blocks kept per query block: g - floor(sparsity*g + 1e-6), in [1,g] */
+  int32_t reserved;
+  int64_t n;           /* T*fh*fw */
+  int64_t n_pad;       /* g*block */
+} da_dims;
+
+/* Layouts written by da_permute. */
+enum {
+  DA_REORDER_ROWS = 0, /* X [B,H,N,d] -> Xp [B,H,n_pad,d]; Xp[slot] = X[pi[slot]], zero rows in pad slots */
+  DA_REORDER_VT = 1,   /* X [B,H,N,d] -> Xt [B,H,g,d,block]; Xt[i][c][s] = X[pi[i*block+s]][c], zeros in pad slots:
+                          the reordered tensor with every block stored transposed (what da_sparse_attn wants for V) */
+  DA_RESTORE = 2       /* Xp [B,H,n_pad,d] -> X [B,H,N,d]; X[n] = Xp[pi^-1[n]] */
+};
+
+/* Host only, pure.  Sizes that follow from the problem (see da_dims). */
+int da_derive(const da_problem* p, da_dims* out /* host */);
+
+/* Host only, pure.  Bytes of scratch da_forward needs for this problem. */
+int da_workspace_size(const da_problem* p, size_t* bytes /* host */);
+
+/*
+ * Algorithm 1 (reorder index) and Algorithm 2 (restore index) as arrays, for callers that
+ * want them; the other entry points compute the index arithmetic on the fly and do not
+ * read these.  perm[n_pad] int32: original token at each slot, -1 in pad slots.
+ * inv[n] int32: slot of each original token.  valid[g] int32: real tokens per block.
+ * Any of the three may be NULL.  Only T, fh, fw, ph, pw of the problem are used.
+ */
+int da_build_perm(const da_problem* p, int32_t* perm, int32_t* inv, int32_t* valid, void* stream);
+
+/*
+ * Definition 3.2.  From Q and K [B,H,N,d] compute
+ *   q_pool, k_pool [B,H,g,d] float : mean over the valid tokens of each block, float32,
+ *       summed in slot order (acc = acc + x, one rounding per add) and divided once by
+ *       the valid count;
+ *   logits [B,H,g,g] float : Q~ K~^T / sqrt(d) in float32 with the fixed order
+ *       acc = acc + (q[c]*k[c]) for c = 0..d-1 (multiply and add rounded separately),
+ *       then one multiply by float(1/sqrt(d));
+ *   draft  [B,H,g,g] float : row softmax of logits (the draft attention map).
+ * q_pool and k_pool are required; logits and draft may each be NULL (then not produced).
+ * Any window ph, pw >= 1 and any d that is a multiple of 8 (bf16) or 4 (f32) is accepted.
+ */
+int da_draft_map(const da_problem* p, const void* Q, const void* K, float* q_pool, float* k_pool,
+                 float* logits, float* draft, void* stream);
+
+/*
+ * Guided sparsity.  For every row of scores [B,H,g,g] (float) keep the k = da_dims.k
+ * largest entries; equal values are kept lowest column first; -0 equals +0; NaN ranks
+ * below every number.  idx [B,H,g,k] int32 receives the kept columns in ascending order.
+ * mask [B,H,g,g] uint8 (may be NULL) receives M_ij in {0,1}.  The order is that of the
+ * draft map whether scores holds logits or their row softmax.
+ */
+int da_select_blocks(const da_problem* p, const float* scores, int32_t* idx, uint8_t* mask, void* stream);
+
+/* Reordering by pi of Algorithm 1 / restoring by pi^-1 of Algorithm 2; `mode` is one of
+ * DA_REORDER_ROWS, DA_REORDER_VT, DA_RESTORE (layouts above).  Pure data movement. */
+int da_permute(const da_problem* p, const void* X, void* Y, int mode, void* stream);
+
+/*
+ * SparseAttn on reordered tensors.  Qp, Kp [B,H,n_pad,d] (DA_REORDER_ROWS), Vt
+ * [B,H,g,d,block] (DA_REORDER_VT), idx [B,H,g,k] int32 with entries in [0,g) (any order,
+ * no repeats).  For query block i: Op[i*block+u] = sum_v softmax_v(Qp[u].Kp[v]/sqrt(d)) V[v]
+ * over the valid slots v of the blocks in idx[i]; dropped blocks and pad keys get
+ * probability 0.  Op [B,H,n_pad,d] in the problem's dtype; rows of pad query slots are
+ * written with unspecified finite values.  lse [B,H,n_pad] float (may be NULL) receives the
+ * natural-log normaliser of each row.
+ * Supported: block == 64 and (dtype, d) in {(DA_BF16, 128), (DA_BF16, 64), (DA_F32, 64),
+ * (DA_F32, 128)}; anything else returns DA_ERR_UNSUPPORTED.  bf16 uses bf16 MFMA with
+ * float32 accumulation and softmax; f32 uses float32 arithmetic throughout.
+ */
+int da_sparse_attn(const da_problem* p, const void* Qp, const void* Kp, const void* Vt,
+                   const int32_t* idx, void* Op, float* lse, void* stream);
+
+/*
+ * The whole path: O = restore(SparseAttn(reorder(Q,K,V), top-k(draft logits))).
+ * Q, K, V, O [B,H,N,d].  idx_out [B,H,g,k] int32 (may be NULL) receives the kept blocks.
+ * ws/ws_bytes: scratch of at least da_workspace_size() bytes, 256-byte aligned.
+ * Same support matrix as da_sparse_attn.
+ */
+int da_forward(const da_problem* p, const void* Q, const void* K, const void* V, void* O,
+               int32_t* idx_out, void* ws, size_t ws_bytes, void* stream);
+
+/* Static string for a da_status value (never NULL). */
+const char* da_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DA_H */

@@ -1,0 +1,68 @@
+// Internal declarations shared by the host API and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "da.h"
+
+namespace da {
+
+// Everything the kernels need to know about one problem (passed by value).
+struct Geo {
+  int B, H, T, fh, fw, d;
+  int ph, pw, gh, gw;
+  int g, block, k;
+  int dtype;
+  long long n, n_pad;
+};
+
+// Block i (in Algorithm 1's frame / patch-row / patch-column order) -> its frame, the
+// token coordinates of its top-left corner and its valid extent.
+struct BlockPos {
+  int f, y0, x0, vh, vw;
+};
+
+__host__ __device__ inline BlockPos block_pos(const Geo& q, int i) {
+  BlockPos b;
+  int per_frame = q.gh * q.gw;
+  b.f = i / per_frame;
+  int r = i - b.f * per_frame;
+  int bi = r / q.gw;
+  int bj = r - bi * q.gw;
+  b.y0 = bi * q.ph;
+  b.x0 = bj * q.pw;
+  b.vh = min(q.ph, q.fh - b.y0);
+  b.vw = min(q.pw, q.fw - b.x0);
+  return b;
+}
+
+__host__ __device__ inline int block_valid(const Geo& q, int i) {
+  BlockPos b = block_pos(q, i);
+  return b.vh * b.vw;
+}
+
+// Original token index -> slot in the reordered sequence (pi^-1 of Algorithm 2).
+__host__ __device__ inline long long token_slot(const Geo& q, long long n) {
+  int per = q.fh * q.fw;
+  int f = (int)(n / per);
+  int r = (int)(n - (long long)f * per);
+  int y = r / q.fw, x = r - y * q.fw;
+  int bi = y / q.ph, u = y - bi * q.ph;
+  int bj = x / q.pw, v = x - bj * q.pw;
+  int vw = min(q.pw, q.fw - bj * q.pw);
+  long long blk = ((long long)f * q.gh + bi) * q.gw + bj;
+  return blk * q.block + u * vw + v;
+}
+
+// launchers (each returns hipGetLastError() after its launches)
+hipError_t launch_build_perm(const Geo& q, int32_t* perm, int32_t* inv, int32_t* valid, hipStream_t s);
+hipError_t launch_permute(const Geo& q, const void* X, void* Y, int mode, hipStream_t s);
+hipError_t launch_pool(const Geo& q, const void* Q, const void* K, float* q_pool, float* k_pool, hipStream_t s);
+hipError_t launch_draft_logits(const Geo& q, const float* q_pool, const float* k_pool, float* logits, hipStream_t s);
+hipError_t launch_row_softmax(const Geo& q, const float* logits, float* draft, hipStream_t s);
+hipError_t launch_select(const Geo& q, const float* scores, int32_t* idx, uint8_t* mask, hipStream_t s);
+hipError_t launch_attn_f32(const Geo& q, const float* Qp, const float* Kp, const float* Vt, const int32_t* idx,
+                           float* Op, float* lse, hipStream_t s);
+hipError_t launch_attn_bf16(const Geo& q, const void* Qp, const void* Kp, const void* Vt, const int32_t* idx,
+                            void* Op, float* lse, hipStream_t s);
+
+}  // namespace da

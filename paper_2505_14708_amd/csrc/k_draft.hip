@@ -1,0 +1,122 @@
+// Draft logits L = Q~ K~^T / sqrt(d) and the draft attention map softmax(L) (Definition 3.2).
+//
+// The kept-block decision is taken from these logits, so they are evaluated in float32 with
+// one fixed order that a CPU can repeat bit for bit: acc = acc + (q[c]*k[c]) for c ascending,
+// the multiply and the add rounded separately (no fused multiply-add, no matrix cores, no
+// split sums), then one multiply by float(1/sqrt(d)).  The work is a register-tiled product
+// on the vector ALUs: a workgroup owns a 128x128 tile of L, a thread an 8x8 piece; Q~ and K~
+// pieces go through LDS transposed so a thread reads its 8 rows / 8 columns as 16-byte loads.
+#include <math.h>
+#include "da_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace da {
+
+constexpr int TM = 128;   // tile rows (query blocks) and columns (key blocks)
+constexpr int TC = 16;    // channels per LDS stage
+
+__global__ __launch_bounds__(256) void draft_logits_kernel(Geo q, const float* __restrict__ q_pool,
+                                                           const float* __restrict__ k_pool, float* __restrict__ logits,
+                                                           float scale) {
+  __shared__ __attribute__((aligned(16))) float qs[TC][TM];
+  __shared__ __attribute__((aligned(16))) float ks[TC][TM];
+  const int tid = threadIdx.x;
+  const int tx = tid & 15, ty = tid >> 4;
+  const long long bh = blockIdx.z;
+  const int row0 = blockIdx.y * TM, col0 = blockIdx.x * TM;
+  const float* qb = q_pool + bh * (long long)q.g * q.d;
+  const float* kb = k_pool + bh * (long long)q.g * q.d;
+  float acc[8][8];
+#pragma unroll
+  for (int a = 0; a < 8; ++a)
+#pragma unroll
+    for (int b = 0; b < 8; ++b) acc[a][b] = 0.f;
+
+  // loader: thread -> (row r = tid/2, half of the TC channels)
+  const int lr = tid >> 1, lc = (tid & 1) * (TC / 2);
+  for (int c0 = 0; c0 < q.d; c0 += TC) {
+    {
+      int gr = row0 + lr, gc = col0 + lr;
+#pragma unroll
+      for (int j = 0; j < TC / 2; ++j) {
+        int c = c0 + lc + j;
+        float qv = (gr < q.g && c < q.d) ? qb[(long long)gr * q.d + c] : 0.f;
+        float kv = (gc < q.g && c < q.d) ? kb[(long long)gc * q.d + c] : 0.f;
+        qs[lc + j][lr] = qv;
+        ks[lc + j][lr] = kv;
+      }
+    }
+    __syncthreads();
+    const int cend = min(TC, q.d - c0);
+    for (int c = 0; c < cend; ++c) {
+      float a[8], b[8];
+      // rows ty*4..+3 and 64+ty*4..+3; columns tx*4..+3 and 64+tx*4..+3
+      *(float4*)&a[0] = *(const float4*)&qs[c][ty * 4];
+      *(float4*)&a[4] = *(const float4*)&qs[c][64 + ty * 4];
+      *(float4*)&b[0] = *(const float4*)&ks[c][tx * 4];
+      *(float4*)&b[4] = *(const float4*)&ks[c][64 + tx * 4];
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = __fadd_rn(acc[i][j], __fmul_rn(a[i], b[j]));
+    }
+    __syncthreads();
+  }
+  float* out = logits + bh * (long long)q.g * q.g;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    int r = row0 + (i < 4 ? ty * 4 + i : 64 + ty * 4 + (i - 4));
+    if (r >= q.g) continue;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      int c = col0 + (j < 4 ? tx * 4 + j : 64 + tx * 4 + (j - 4));
+      if (c < q.g) out[(long long)r * q.g + c] = __fmul_rn(acc[i][j], scale);
+    }
+  }
+}
+
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// One wavefront per row; safe in place (every element is read before it is written by the
+// same lane, and rows do not overlap).
+__global__ __launch_bounds__(256) void row_softmax_kernel(const float* logits, float* draft, int g, long long rows) {
+  long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  int lane = threadIdx.x & 63;
+  const float* in = logits + row * g;
+  float* out = draft + row * g;
+  float m = -INFINITY;
+  for (int j = lane; j < g; j += 64) m = fmaxf(m, in[j]);
+  m = wave_max(m);
+  float z = 0.f;
+  for (int j = lane; j < g; j += 64) z += expf(in[j] - m);
+  z = wave_sum(z);
+  float inv = 1.0f / z;
+  for (int j = lane; j < g; j += 64) out[j] = expf(in[j] - m) * inv;
+}
+
+hipError_t launch_draft_logits(const Geo& q, const float* q_pool, const float* k_pool, float* logits, hipStream_t s) {
+  unsigned t = (unsigned)((q.g + TM - 1) / TM);
+  float scale = (float)(1.0 / sqrt((double)q.d));
+  dim3 grid(t, t, (unsigned)(q.B * q.H));
+  hipLaunchKernelGGL(draft_logits_kernel, grid, dim3(256), 0, s, q, q_pool, k_pool, logits, scale);
+  return hipGetLastError();
+}
+
+hipError_t launch_row_softmax(const Geo& q, const float* logits, float* draft, hipStream_t s) {
+  long long rows = (long long)q.B * q.H * q.g;
+  hipLaunchKernelGGL(row_softmax_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, logits, draft, q.g, rows);
+  return hipGetLastError();
+}
+
+}  // namespace da

@@ -1,0 +1,94 @@
+// Average pooling of Q and K inside each latent frame (Definition 3.2).
+// HBM-bound: Q and K are read once in 16-byte pieces straight from the original layout
+// (the tokens of a patch row are contiguous); each lane owns a fixed group of channels of
+// one block and adds the block's tokens in slot order, so the float32 result does not
+// depend on the launch shape:  acc = acc + x (one rounding per add), mean = acc / valid.
+#include "da_internal.h"
+
+namespace da {
+
+template <int DT>
+struct Vec;
+template <>
+struct Vec<DA_BF16> {
+  static constexpr int N = 8;
+  __device__ static void widen(const uint4& r, float* f) {
+    const unsigned w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      f[2 * j] = __uint_as_float(w[j] << 16);
+      f[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+    }
+  }
+};
+template <>
+struct Vec<DA_F32> {
+  static constexpr int N = 4;
+  __device__ static void widen(const uint4& r, float* f) {
+    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
+    f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+  }
+};
+
+// grid.x covers (bh, block, chunk) items; grid.y = 0 for Q, 1 for K.
+template <int DT>
+__global__ __launch_bounds__(256) void pool_kernel(Geo q, const uint4* __restrict__ Q, const uint4* __restrict__ K,
+                                                   float* __restrict__ q_pool, float* __restrict__ k_pool, int cpr,
+                                                   long long items) {
+  constexpr int N = Vec<DT>::N;
+  long long item = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (item >= items) return;
+  const uint4* X = blockIdx.y ? K : Q;
+  float* out = blockIdx.y ? k_pool : q_pool;
+  long long blk = item / cpr;  // over bh * g
+  int c = (int)(item - blk * cpr);
+  long long bh = blk / q.g;
+  int i = (int)(blk - bh * q.g);
+  BlockPos b = block_pos(q, i);
+  const uint4* src = X + (bh * q.n + ((long long)b.f * q.fh + b.y0) * q.fw + b.x0) * cpr + c;
+  float acc[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) acc[j] = 0.f;
+  for (int u = 0; u < b.vh; ++u) {
+    const uint4* row = src + (long long)u * q.fw * cpr;
+    int v = 0;
+    for (; v + 8 <= b.vw; v += 8) {  // eight independent loads in flight, added in order
+      uint4 r[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) r[t] = row[(long long)(v + t) * cpr];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        float f[N];
+        Vec<DT>::widen(r[t], f);
+#pragma unroll
+        for (int j = 0; j < N; ++j) acc[j] = __fadd_rn(acc[j], f[j]);
+      }
+    }
+    for (; v < b.vw; ++v) {
+      float f[N];
+      Vec<DT>::widen(row[(long long)v * cpr], f);
+#pragma unroll
+      for (int j = 0; j < N; ++j) acc[j] = __fadd_rn(acc[j], f[j]);
+    }
+  }
+  float cnt = (float)(b.vh * b.vw);
+  float* dst = out + blk * q.d + c * N;
+#pragma unroll
+  for (int j = 0; j < N; ++j) dst[j] = __fdiv_rn(acc[j], cnt);
+}
+
+hipError_t launch_pool(const Geo& q, const void* Q, const void* K, float* q_pool, float* k_pool, hipStream_t s) {
+  size_t es = q.dtype == DA_BF16 ? 2 : 4;
+  int cpr = (int)(q.d * es / 16);
+  long long items = (long long)q.B * q.H * q.g * cpr;
+  dim3 grid((unsigned)((items + 255) / 256), 2);
+  if (q.dtype == DA_BF16)
+    hipLaunchKernelGGL(pool_kernel<DA_BF16>, grid, dim3(256), 0, s, q, (const uint4*)Q, (const uint4*)K, q_pool, k_pool,
+                       cpr, items);
+  else
+    hipLaunchKernelGGL(pool_kernel<DA_F32>, grid, dim3(256), 0, s, q, (const uint4*)Q, (const uint4*)K, q_pool, k_pool,
+                       cpr, items);
+  return hipGetLastError();
+}
+
+}  // namespace da

@@ -1,0 +1,85 @@
+// Guided sparsity: per row of the draft scores keep the k largest entries (ties to the
+// lowest column) and emit their columns in ascending order.
+//
+// One wavefront per row.  The row is mapped to order-preserving 32-bit keys held in LDS; the
+// value of the k-th largest key is found bit by bit from the top (32 counting passes over
+// LDS, each a wave-wide popcount reduction); one more ordered pass writes every column
+// whose key beats the threshold plus the first (k - #greater) columns that equal it, using
+// ballot + lane-prefix popcounts so the output stays in column order without any sort.
+#include "da_internal.h"
+
+namespace da {
+
+__device__ inline unsigned order_key(float x) {
+  unsigned u = __float_as_uint(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0u;       // NaN ranks below everything
+  if ((u & 0x7fffffffu) == 0u) u = 0u;                  // -0 == +0
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ inline int wave_sum_int(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// number of set bits of `m` strictly below this lane
+__device__ inline int lane_prefix(unsigned long long m) {
+  return __builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0));
+}
+
+template <bool IN_LDS>
+__global__ __launch_bounds__(64) void select_kernel(const float* __restrict__ scores, int32_t* __restrict__ idx,
+                                                    uint8_t* __restrict__ mask, int g, int k) {
+  extern __shared__ unsigned lds_keys[];
+  const long long row = blockIdx.x;
+  const int lane = threadIdx.x;
+  const float* in = scores + row * g;
+  // without room in LDS the keys are recomputed from global memory in every pass
+  auto key_at = [&](int j) -> unsigned { return IN_LDS ? lds_keys[j] : order_key(in[j]); };
+  if (IN_LDS) {
+    for (int j = lane; j < g; j += 64) lds_keys[j] = order_key(in[j]);
+    __syncthreads();
+  }
+  unsigned thr = 0u;
+  for (int bit = 31; bit >= 0; --bit) {
+    unsigned cand = thr | (1u << bit);
+    int cnt = 0;
+    for (int j = lane; j < g; j += 64) cnt += key_at(j) >= cand ? 1 : 0;
+    cnt = wave_sum_int(cnt);
+    if (cnt >= k) thr = cand;
+  }
+  // thr is now the k-th largest key
+  int gt = 0;
+  for (int j = lane; j < g; j += 64) gt += key_at(j) > thr ? 1 : 0;
+  gt = wave_sum_int(gt);
+  int need_eq = k - gt;
+  int written = 0, eq_seen = 0;
+  int32_t* out = idx + row * k;
+  uint8_t* mrow = mask ? mask + row * g : nullptr;
+  for (int j0 = 0; j0 < g; j0 += 64) {
+    int j = j0 + lane;
+    unsigned key = j < g ? key_at(j) : 0u;
+    bool is_gt = j < g && key > thr;
+    bool is_eq = j < g && key == thr;
+    unsigned long long eq_mask = __ballot(is_eq);
+    bool take = is_gt || (is_eq && eq_seen + lane_prefix(eq_mask) < need_eq);
+    unsigned long long take_mask = __ballot(take);
+    if (take) out[written + lane_prefix(take_mask)] = j;
+    if (mrow && j < g) mrow[j] = take ? 1 : 0;
+    written += __popcll(take_mask);
+    eq_seen += __popcll(eq_mask);
+  }
+}
+
+hipError_t launch_select(const Geo& q, const float* scores, int32_t* idx, uint8_t* mask, hipStream_t s) {
+  long long rows = (long long)q.B * q.H * q.g;
+  size_t lds = (size_t)q.g * sizeof(unsigned);
+  if (lds <= 64 * 1024)
+    hipLaunchKernelGGL(select_kernel<true>, dim3((unsigned)rows), dim3(64), lds, s, scores, idx, mask, q.g, q.k);
+  else
+    hipLaunchKernelGGL(select_kernel<false>, dim3((unsigned)rows), dim3(64), 0, s, scores, idx, mask, q.g, q.k);
+  return hipGetLastError();
+}
+
+}  // namespace da

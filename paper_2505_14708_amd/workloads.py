@@ -135,17 +135,29 @@ def make_head(w: Workload, b: int, h: int):
     return to_storage(q, w.dtype), to_storage(k, w.dtype), to_storage(v, w.dtype)
 
 
-def make_qkv(w: Workload, heads=None):
+def make_qkv(w: Workload, heads=None, threads: int = 8):
     """Q, K, V for the whole problem, [B, H', N, d] in storage format.
 
     ``heads`` (an iterable of head numbers) restricts generation to those heads, in
-    that order; each head's content depends only on (seed, b, h).
+    that order; each head's content depends only on (seed, b, h).  Heads are made on a
+    small thread pool (NumPy releases the GIL in the heavy parts); no processes are
+    started, so this is safe to call from a process that already uses the GPU.
     """
+    from concurrent.futures import ThreadPoolExecutor
     heads = list(range(w.H)) if heads is None else list(heads)
     np_dtype = np.float32 if w.dtype == F32 else np.uint16
     shape = (w.B, len(heads), w.N, w.d)
     Q, K, V = (np.empty(shape, np_dtype) for _ in range(3))
-    for b in range(w.B):
-        for i, h in enumerate(heads):
-            Q[b, i], K[b, i], V[b, i] = make_head(w, b, h)
+
+    def one(job):
+        b, i, h = job
+        Q[b, i], K[b, i], V[b, i] = make_head(w, b, h)
+
+    jobs = [(b, i, h) for b in range(w.B) for i, h in enumerate(heads)]
+    if threads <= 1 or len(jobs) == 1:
+        for job in jobs:
+            one(job)
+    else:
+        with ThreadPoolExecutor(min(threads, len(jobs))) as ex:
+            list(ex.map(one, jobs))
     return Q, K, V

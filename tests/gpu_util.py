@@ -1,0 +1,135 @@
+"""Helpers shared by the GPU parity tests: host <-> device movement of stored tensors and
+oracle-side references.  No method arithmetic lives here."""
+from __future__ import annotations
+
+import sys
+
+import numpy as np
+
+from oracle import draft_attention as oa
+from paper_2505_14708_amd import binding as da
+from paper_2505_14708_amd import workloads as W
+
+
+def say(msg):
+    """Progress line, flushed, so a stuck GPU step names itself."""
+    print(f"[gpu-test] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def to_dev(x: np.ndarray, dtype: int):
+    """Stored array (float32 values or uint16 bf16 bits) -> CUDA tensor of that storage type."""
+    import torch
+    if dtype == W.F32:
+        return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.uint16).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def to_host_storage(t, dtype: int) -> np.ndarray:
+    """CUDA tensor -> stored array in the oracle's convention (bf16 as uint16 bits)."""
+    import torch
+    if dtype == W.F32:
+        return t.detach().cpu().numpy()
+    return t.detach().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def to_host_f64(t, dtype: int) -> np.ndarray:
+    return W.storage_to_f64(to_host_storage(t, dtype), dtype)
+
+
+def empty(shape, dtype: int):
+    import torch
+    return torch.empty(shape, dtype=torch.float32 if dtype == W.F32 else torch.bfloat16, device="cuda")
+
+
+def vt_to_rows(vt: np.ndarray, g: int, d: int, block: int) -> np.ndarray:
+    """[.., g, d, block] block-transposed layout -> [.., g*block, d] rows (a pure reshape)."""
+    lead = vt.shape[:-3] if vt.ndim > 3 else ()
+    x = vt.reshape(lead + (g, d, block))
+    return np.swapaxes(x, -1, -2).reshape(lead + (g * block, d))
+
+
+class HeadRef:
+    """Oracle intermediates for one head of a workload (computed lazily, cached)."""
+
+    def __init__(self, w: W.Workload, q, k, v, keep_blocks=0):
+        self.w, self.q, self.k, self.v = w, q, k, v
+        self.dims = oa.derive_dims(w.T, w.fh, w.fw, w.ph, w.pw, w.sparsity, keep_blocks)
+        self.perm, self.valid = oa.reorder_index(w.T, w.fh, w.fw, w.ph, w.pw)
+        self.inv = oa.restore_index(self.perm, self.dims["n"])
+        self._cache = {}
+
+    def _get(self, key, fn):
+        if key not in self._cache:
+            self._cache[key] = fn()
+        return self._cache[key]
+
+    @property
+    def block(self):
+        return self.dims["block"]
+
+    @property
+    def q_pool(self):
+        return self._get("qp", lambda: oa.pool_canonical_f32(oa.widen_f32(self.q, self.w.dtype), self.perm,
+                                                             self.valid, self.block))
+
+    @property
+    def k_pool(self):
+        return self._get("kp", lambda: oa.pool_canonical_f32(oa.widen_f32(self.k, self.w.dtype), self.perm,
+                                                             self.valid, self.block))
+
+    @property
+    def logits(self):
+        return self._get("L", lambda: oa.draft_logits_canonical_f32(self.q_pool, self.k_pool))
+
+    @property
+    def sel(self):
+        return self._get("sel", lambda: oa.select_blocks(self.logits, self.dims["k"]))
+
+    @property
+    def idx(self):
+        return self.sel[0]
+
+    @property
+    def mask(self):
+        return self.sel[1]
+
+    def permuted64(self, which):
+        x = {"q": self.q, "k": self.k, "v": self.v}[which]
+        return self._get("p64" + which, lambda: oa.permute(oa.widen_f64(x, self.w.dtype), self.perm))
+
+    def attention(self, rows=None, idx=None, want_lse=False):
+        idx = self.idx if idx is None else idx
+        return oa.sparse_attention_blocks(self.permuted64("q"), self.permuted64("k"), self.permuted64("v"), idx,
+                                          self.valid, self.block, rows=rows, want_lse=want_lse)
+
+    def near_ties(self, tol=1e-6):
+        """Rows whose k-th and (k+1)-th float64 logits are closer than tol (for attributing a mismatch)."""
+        k = self.dims["k"]
+        if k >= self.dims["g"]:
+            return 0
+        qp = oa.pool_f64(oa.widen_f64(self.q, self.w.dtype), self.perm, self.valid, self.block)
+        kp = oa.pool_f64(oa.widen_f64(self.k, self.w.dtype), self.perm, self.valid, self.block)
+        L = np.sort(oa.draft_logits_f64(qp, kp), axis=1)[:, ::-1]
+        return int((L[:, k - 1] - L[:, k] < tol).sum())
+
+
+def output_error(got64: np.ndarray, ref64: np.ndarray):
+    diff = np.abs(got64 - ref64)
+    return float(diff.max()), float(diff.mean())
+
+
+# tolerances stated by the build target: bf16 outputs max-abs 2e-2 / mean-abs 2e-3, f32 1e-4
+TOL = {W.BF16: (2e-2, 2e-3), W.F32: (1e-4, 1e-4)}
+
+
+def stratified_rows(ref: HeadRef, per_class=4, seed=0):
+    """Query blocks covering first/last frame, interior and every edge-block class."""
+    rng = np.random.default_rng(seed)
+    g = ref.dims["g"]
+    per_frame = ref.dims["gh"] * ref.dims["gw"]
+    rows = {0, g - 1, per_frame - 1, g - per_frame}
+    for nv in sorted(set(ref.valid)):
+        cand = np.nonzero(ref.valid == nv)[0]
+        rows.update(int(x) for x in rng.choice(cand, size=min(per_class, len(cand)), replace=False))
+    return sorted(rows)

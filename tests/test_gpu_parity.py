@@ -1,0 +1,325 @@
+"""GPU parity: every stage of the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Integer / byte / index results must be bit-exact; floating-point
+outputs must be within the stated tolerances (bf16: max-abs 2e-2, mean-abs 2e-3; f32: 1e-4).
+
+Sizes here finish in seconds on the oracle yet span several tiles and ragged tails:
+partial edge blocks of 48 / 40 / 32 / 24 valid slots, g not a multiple of any tile size."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import draft_attention as oa
+from paper_2505_14708_amd import binding as da
+from paper_2505_14708_amd import workloads as W
+from gpu_util import (HeadRef, TOL, empty, output_error, say, stratified_rows, to_dev, to_host_f64,
+                      to_host_storage, vt_to_rows)
+
+pytestmark = pytest.mark.gpu
+
+SMALL = {
+    "tiny_fp32": W.CONFIGS["tiny_fp32"],
+    "bf16_480p_T3": W.CONFIGS["480p"].with_(name="bf16_480p_T3", H=2, T=3, sparsity=0.75),
+    "bf16_720p_T2": W.CONFIGS["720p_hunyuan"].with_(name="bf16_720p_T2", H=2, T=2, sparsity=0.9),
+    "f32_ragged": W.Workload("f32_ragged", B=2, H=1, d=64, T=2, fh=20, fw=12, sparsity=0.4, dtype=W.F32, seed=3),
+    "bf16_one_block": W.Workload("bf16_one_block", B=1, H=1, d=128, T=1, fh=5, fw=3, sparsity=0.0, seed=4),
+}
+
+
+@pytest.fixture(scope="module")
+def torch_mod():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+@pytest.fixture(scope="module")
+def cases():
+    """name -> (workload, Q, K, V stored arrays [B,H,N,d], {(b,h): HeadRef})"""
+    out = {}
+    for name, w in SMALL.items():
+        Q, K, V = W.make_qkv(w)
+        refs = {(b, h): HeadRef(w, Q[b, h], K[b, h], V[b, h]) for b in range(w.B) for h in range(w.H)}
+        out[name] = (w, Q, K, V, refs)
+    return out
+
+
+def _names():
+    return list(SMALL.keys())
+
+
+# ----------------------------------------------------------------------------- Algorithm 1 / 2
+@pytest.mark.parametrize("shape", [(2, 30, 52, 8, 8), (3, 45, 80, 8, 8), (2, 16, 16, 8, 8), (2, 5, 7, 2, 3),
+                                   (1, 4, 4, 2, 2), (2, 9, 9, 8, 8), (2, 6, 5, 1, 1)])
+def test_build_perm_bit_exact(torch_mod, shape):
+    torch = torch_mod
+    T, fh, fw, ph, pw = shape
+    say(f"build_perm {shape}")
+    p = da.problem(1, 1, T, fh, fw, 128, ph, pw)
+    dims = da.da_derive(p)
+    perm = torch.full((dims.n_pad,), -7, dtype=torch.int32, device="cuda")
+    inv = torch.full((dims.n,), -7, dtype=torch.int32, device="cuda")
+    valid = torch.full((dims.g,), -7, dtype=torch.int32, device="cuda")
+    da.da_build_perm(p, perm, inv, valid)
+    torch.cuda.synchronize()
+    rperm, rvalid = oa.reorder_index(T, fh, fw, ph, pw)
+    assert np.array_equal(perm.cpu().numpy(), rperm)
+    assert np.array_equal(valid.cpu().numpy(), rvalid)
+    assert np.array_equal(inv.cpu().numpy(), oa.restore_index(rperm, dims.n))
+
+
+# ----------------------------------------------------------------------------- reorder / restore
+@pytest.mark.parametrize("name", _names())
+def test_permute_bit_exact(torch_mod, cases, name):
+    torch = torch_mod
+    w, Q, K, V, refs = cases[name]
+    say(f"permute {name}")
+    p = da.problem_of(w)
+    dims = da.da_derive(p)
+    x = to_dev(V, w.dtype)
+    rows = empty((w.B, w.H, dims.n_pad, w.d), w.dtype)
+    vt = empty((w.B, w.H, dims.g, w.d, dims.block), w.dtype)
+    back = empty((w.B, w.H, dims.n, w.d), w.dtype)
+    rows.fill_(7.0); vt.fill_(7.0); back.fill_(7.0)
+    da.da_permute(p, x, rows, da.DA_REORDER_ROWS)
+    da.da_permute(p, x, vt, da.DA_REORDER_VT)
+    da.da_permute(p, rows, back, da.DA_RESTORE)
+    torch.cuda.synchronize()
+    hrows, hvt, hback = (to_host_storage(t, w.dtype) for t in (rows, vt, back))
+    for (b, h), ref in refs.items():
+        want = oa.permute(V[b, h], ref.perm)
+        assert np.array_equal(hrows[b, h], want)
+        assert np.array_equal(vt_to_rows(hvt[b, h], dims.g, w.d, dims.block), want)
+        assert np.array_equal(hback[b, h], oa.restore(want, ref.inv))
+    assert np.array_equal(hback, V)          # restore(reorder(X)) == X
+
+
+def test_permute_other_windows(torch_mod):
+    torch = torch_mod
+    for (T, fh, fw, ph, pw, d, dt) in [(2, 5, 7, 2, 3, 8, W.BF16), (2, 6, 5, 1, 1, 4, W.F32), (1, 16, 32, 8, 16, 64, W.BF16)]:
+        say(f"permute window {ph}x{pw}")
+        rng = np.random.default_rng(5)
+        n = T * fh * fw
+        X = W.to_storage(rng.normal(size=(1, 2, n, d)), dt)
+        p = da.problem(1, 2, T, fh, fw, d, ph, pw, dtype=dt)
+        dims = da.da_derive(p)
+        rows = empty((1, 2, dims.n_pad, d), dt)
+        back = empty((1, 2, n, d), dt)
+        da.da_permute(p, to_dev(X, dt), rows, da.DA_REORDER_ROWS)
+        da.da_permute(p, rows, back, da.DA_RESTORE)
+        torch.cuda.synchronize()
+        perm, _ = oa.reorder_index(T, fh, fw, ph, pw)
+        for h in range(2):
+            assert np.array_equal(to_host_storage(rows, dt)[0, h], oa.permute(X[0, h], perm))
+        assert np.array_equal(to_host_storage(back, dt), X)
+
+
+# ----------------------------------------------------------------------------- Definition 3.2
+@pytest.mark.parametrize("name", _names())
+def test_draft_map_stage(torch_mod, cases, name):
+    torch = torch_mod
+    w, Q, K, V, refs = cases[name]
+    say(f"draft_map {name}")
+    p = da.problem_of(w)
+    dims = da.da_derive(p)
+    g = dims.g
+    qp = torch.empty((w.B, w.H, g, w.d), dtype=torch.float32, device="cuda")
+    kp = torch.empty_like(qp)
+    logits = torch.empty((w.B, w.H, g, g), dtype=torch.float32, device="cuda")
+    draft = torch.empty_like(logits)
+    da.da_draft_map(p, to_dev(Q, w.dtype), to_dev(K, w.dtype), qp, kp, logits, draft)
+    torch.cuda.synchronize()
+    hq, hk, hl, hd = (t.cpu().numpy() for t in (qp, kp, logits, draft))
+    for (b, h), ref in refs.items():
+        assert np.array_equal(hq[b, h].view(np.uint32), ref.q_pool.view(np.uint32)), "pooled Q bits"
+        assert np.array_equal(hk[b, h].view(np.uint32), ref.k_pool.view(np.uint32)), "pooled K bits"
+        assert np.array_equal(hl[b, h].view(np.uint32), ref.logits.view(np.uint32)), "draft logit bits"
+        q64 = oa.pool_f64(oa.widen_f64(Q[b, h], w.dtype), ref.perm, ref.valid, ref.block)
+        k64 = oa.pool_f64(oa.widen_f64(K[b, h], w.dtype), ref.perm, ref.valid, ref.block)
+        A = oa.draft_map(q64, k64)
+        assert np.abs(hd[b, h] - A).max() < 1e-5
+        assert np.abs(hd[b, h].sum(axis=1) - 1.0).max() < 1e-5
+    # draft alone (logits == NULL) gives the same map
+    draft2 = torch.empty_like(draft)
+    da.da_draft_map(p, to_dev(Q, w.dtype), to_dev(K, w.dtype), qp, kp, None, draft2)
+    torch.cuda.synchronize()
+    assert torch.equal(draft, draft2)
+
+
+def test_draft_map_window_1x1_is_token_level_map(torch_mod):
+    torch = torch_mod
+    say("draft_map 1x1")
+    T, fh, fw, d = 2, 6, 5, 8
+    rng = np.random.default_rng(6)
+    n = T * fh * fw
+    Q = rng.normal(size=(1, 1, n, d)).astype(np.float32)
+    K = rng.normal(size=(1, 1, n, d)).astype(np.float32)
+    p = da.problem(1, 1, T, fh, fw, d, 1, 1, dtype=da.DA_F32)
+    qp = torch.empty((1, 1, n, d), dtype=torch.float32, device="cuda")
+    kp = torch.empty_like(qp)
+    draft = torch.empty((1, 1, n, n), dtype=torch.float32, device="cuda")
+    da.da_draft_map(p, to_dev(Q, W.F32), to_dev(K, W.F32), qp, kp, None, draft)
+    torch.cuda.synchronize()
+    assert np.array_equal(qp.cpu().numpy(), Q)
+    ref = oa.softmax_rows(Q[0, 0].astype(np.float64) @ K[0, 0].astype(np.float64).T / np.sqrt(d))
+    assert np.abs(draft.cpu().numpy()[0, 0] - ref).max() < 1e-5
+
+
+# ----------------------------------------------------------------------------- selection
+@pytest.mark.parametrize("name", _names())
+def test_select_on_oracle_logits(torch_mod, cases, name):
+    torch = torch_mod
+    w, Q, K, V, refs = cases[name]
+    say(f"select {name}")
+    p = da.problem_of(w)
+    dims = da.da_derive(p)
+    L = np.stack([np.stack([refs[(b, h)].logits for h in range(w.H)]) for b in range(w.B)])
+    idx = torch.full((w.B, w.H, dims.g, dims.k), -1, dtype=torch.int32, device="cuda")
+    mask = torch.full((w.B, w.H, dims.g, dims.g), 9, dtype=torch.uint8, device="cuda")
+    da.da_select_blocks(p, torch.from_numpy(L).cuda(), idx, mask)
+    torch.cuda.synchronize()
+    for (b, h), ref in refs.items():
+        assert np.array_equal(idx.cpu().numpy()[b, h], ref.idx), f"near-ties: {ref.near_ties()}"
+        assert np.array_equal(mask.cpu().numpy()[b, h], ref.mask)
+
+
+def test_select_planted_rows(torch_mod):
+    torch = torch_mod
+    say("select planted")
+    rng = np.random.default_rng(7)
+    for (g, k) in [(7, 1), (7, 7), (64, 5), (65, 33), (200, 37), (1000, 100), (3900, 390)]:
+        L = rng.normal(size=(g, g)).astype(np.float32)
+        L[0, :] = 0.0                                   # all equal
+        L[1, :] = np.round(L[1] * 2) / 2                # many duplicates
+        L[2, ::2] = 0.0; L[2, 1::2] = -0.0              # signed zeros tie
+        L[3, :] = -np.arange(g, dtype=np.float32)       # descending
+        L[4, :] = np.arange(g, dtype=np.float32)        # ascending
+        L[5, : g // 2] = -np.inf
+        L[min(6, g - 1), -1] = np.inf
+        T = g                                           # g blocks: T frames of one 8x8 patch
+        p = da.problem(1, 1, T, 8, 8, 128, keep_blocks=k)
+        assert da.da_derive(p).g == g and da.da_derive(p).k == k
+        idx = torch.empty((g, k), dtype=torch.int32, device="cuda")
+        mask = torch.empty((g, g), dtype=torch.uint8, device="cuda")
+        da.da_select_blocks(p, torch.from_numpy(L).cuda(), idx, mask)
+        torch.cuda.synchronize()
+        ridx, rmask = oa.select_blocks(L, k)
+        assert np.array_equal(idx.cpu().numpy(), ridx), (g, k)
+        assert np.array_equal(mask.cpu().numpy(), rmask), (g, k)
+
+
+# ----------------------------------------------------------------------------- SparseAttn
+def _attn_inputs(torch, w, Q, K, V, refs, idx_np):
+    p = da.problem_of(w)
+    dims = da.da_derive(p)
+    Qp = empty((w.B, w.H, dims.n_pad, w.d), w.dtype)
+    Kp = empty((w.B, w.H, dims.n_pad, w.d), w.dtype)
+    Vt = empty((w.B, w.H, dims.g, w.d, dims.block), w.dtype)
+    da.da_permute(p, to_dev(Q, w.dtype), Qp, da.DA_REORDER_ROWS)
+    da.da_permute(p, to_dev(K, w.dtype), Kp, da.DA_REORDER_ROWS)
+    da.da_permute(p, to_dev(V, w.dtype), Vt, da.DA_REORDER_VT)
+    idx = torch.from_numpy(idx_np.astype(np.int32)).cuda()
+    return p, dims, Qp, Kp, Vt, idx
+
+
+@pytest.mark.parametrize("name", _names())
+def test_sparse_attn_stage(torch_mod, cases, name):
+    torch = torch_mod
+    w, Q, K, V, refs = cases[name]
+    say(f"sparse_attn {name}")
+    idx_np = np.stack([np.stack([refs[(b, h)].idx for h in range(w.H)]) for b in range(w.B)])
+    p, dims, Qp, Kp, Vt, idx = _attn_inputs(torch, w, Q, K, V, refs, idx_np)
+    Op = empty((w.B, w.H, dims.n_pad, w.d), w.dtype)
+    lse = torch.empty((w.B, w.H, dims.n_pad), dtype=torch.float32, device="cuda")
+    da.da_sparse_attn(p, Qp, Kp, Vt, idx, Op, lse)
+    torch.cuda.synchronize()
+    got = to_host_f64(Op, w.dtype)
+    assert np.isfinite(got).all()                       # pad query rows too
+    tol_max, tol_mean = TOL[w.dtype]
+    for (b, h), ref in refs.items():
+        want, want_lse = ref.attention(want_lse=True)
+        real = ref.perm >= 0
+        emax, emean = output_error(got[b, h][real], want[real])
+        say(f"  {name} head {(b, h)}: max-abs {emax:.3e} mean-abs {emean:.3e}")
+        assert emax <= tol_max and emean <= tol_mean
+        lerr = np.abs(lse.cpu().numpy()[b, h][real] - want_lse[real]).max()
+        assert lerr < (2e-2 if w.dtype == W.BF16 else 1e-4)
+
+
+def test_sparse_attn_list_order_and_dense_case(torch_mod, cases):
+    """Shuffled lists give the same result to rounding; k = g equals full attention (Definition 3.1)."""
+    torch = torch_mod
+    w, Q, K, V, refs = cases["bf16_480p_T3"]
+    say("sparse_attn shuffled lists / dense")
+    ref = refs[(0, 0)]
+    g = ref.dims["g"]
+    rng = np.random.default_rng(8)
+    w1 = w.with_(H=1)
+    idx_sh = np.stack([rng.permutation(row) for row in ref.idx])[None, None]
+    p, dims, Qp, Kp, Vt, idx = _attn_inputs(torch, w1, Q[:, :1], K[:, :1], V[:, :1], refs, idx_sh)
+    Op = empty((1, 1, dims.n_pad, w.d), w.dtype)
+    da.da_sparse_attn(p, Qp, Kp, Vt, idx, Op, None)
+    torch.cuda.synchronize()
+    real = ref.perm >= 0
+    emax, emean = output_error(to_host_f64(Op, w.dtype)[0, 0][real], ref.attention()[real])
+    assert emax <= 2e-2 and emean <= 2e-3
+    # dense: every block kept
+    wd = w1.with_(sparsity=0.0)
+    pd = da.problem_of(wd)
+    assert da.da_derive(pd).k == g
+    idx_all = torch.arange(g, dtype=torch.int32, device="cuda").repeat(g, 1).contiguous()
+    da.da_sparse_attn(pd, Qp, Kp, Vt, idx_all, Op, None)
+    torch.cuda.synchronize()
+    full = oa.full_attention(*(oa.widen_f64(x[0, 0], w.dtype) for x in (Q, K, V)))
+    got = oa.restore(to_host_f64(Op, w.dtype)[0, 0], ref.inv)
+    emax, emean = output_error(got, full)
+    say(f"  dense k=g: max-abs {emax:.3e} mean-abs {emean:.3e}")
+    assert emax <= 2e-2 and emean <= 2e-3
+
+
+def test_sparse_attn_staged_variant_matches(torch_mod, cases):
+    """The register-staged tile loader builds the same LDS image as the direct-to-LDS one."""
+    torch = torch_mod
+    w, Q, K, V, refs = cases["bf16_720p_T2"]
+    say("sparse_attn staged variant")
+    idx_np = np.stack([np.stack([refs[(b, h)].idx for h in range(w.H)]) for b in range(w.B)])
+    p, dims, Qp, Kp, Vt, idx = _attn_inputs(torch, w, Q, K, V, refs, idx_np)
+    O1 = empty((w.B, w.H, dims.n_pad, w.d), w.dtype)
+    O2 = empty((w.B, w.H, dims.n_pad, w.d), w.dtype)
+    da.da_sparse_attn(p, Qp, Kp, Vt, idx, O1, None)
+    os.environ["DA_ATTN_STAGED"] = "1"
+    try:
+        da.da_sparse_attn(p, Qp, Kp, Vt, idx, O2, None)
+    finally:
+        del os.environ["DA_ATTN_STAGED"]
+    torch.cuda.synchronize()
+    assert torch.equal(O1.view(torch.int16), O2.view(torch.int16))
+
+
+# ----------------------------------------------------------------------------- whole path
+@pytest.mark.parametrize("name", _names())
+def test_forward_end_to_end(torch_mod, cases, name):
+    torch = torch_mod
+    w, Q, K, V, refs = cases[name]
+    say(f"forward {name}")
+    p = da.problem_of(w)
+    dims = da.da_derive(p)
+    ws = torch.empty(da.da_workspace_size(p), dtype=torch.uint8, device="cuda")
+    O = empty((w.B, w.H, dims.n, w.d), w.dtype)
+    idx = torch.full((w.B, w.H, dims.g, dims.k), -1, dtype=torch.int32, device="cuda")
+    da.da_forward(p, to_dev(Q, w.dtype), to_dev(K, w.dtype), to_dev(V, w.dtype), O, ws, idx)
+    torch.cuda.synchronize()
+    got = to_host_f64(O, w.dtype)
+    tol_max, tol_mean = TOL[w.dtype]
+    for (b, h), ref in refs.items():
+        assert np.array_equal(idx.cpu().numpy()[b, h], ref.idx), f"near-ties: {ref.near_ties()}"
+        want = oa.restore(ref.attention(), ref.inv)
+        emax, emean = output_error(got[b, h], want)
+        say(f"  {name} head {(b, h)}: max-abs {emax:.3e} mean-abs {emean:.3e}")
+        assert emax <= tol_max and emean <= tol_mean
+    # a second call without idx_out gives the same bits (deterministic, scratch reuse is clean)
+    O2 = torch.empty_like(O)
+    da.da_forward(p, to_dev(Q, w.dtype), to_dev(K, w.dtype), to_dev(V, w.dtype), O2, ws, None)
+    torch.cuda.synchronize()
+    assert torch.equal(O.view(torch.int16 if w.dtype == W.BF16 else torch.int32),
+                       O2.view(torch.int16 if w.dtype == W.BF16 else torch.int32))

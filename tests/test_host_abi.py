@@ -1,0 +1,107 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, derives the same sizes as the oracle, and rejects bad calls before
+launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import draft_attention as oa
+from paper_2505_14708_amd import binding as da
+from paper_2505_14708_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+pytestmark = pytest.mark.skipif(not os.path.exists(da.LIB_PATH), reason="library not built")
+
+FAKE = 0x10000  # a non-NULL, 16-byte aligned value that is never dereferenced on the error paths
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "da.h")).read()
+    declared = set(re.findall(r"\b(da_[a-z_]+)\s*\(", header))
+    assert declared == set(da.EXPORTS)
+    L = da.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(da.da_problem) == 48 and da.da_problem.sparsity.offset == 40
+    assert ctypes.sizeof(da.da_dims) == 40 and da.da_dims.n.offset == 24
+
+
+def test_derive_matches_oracle_on_all_configs():
+    for w in W.CONFIGS.values():
+        dims = da.da_derive(da.problem_of(w))
+        ref = oa.derive_dims(w.T, w.fh, w.fw, w.ph, w.pw, w.sparsity)
+        got = dict(gh=dims.gh, gw=dims.gw, g=dims.g, block=dims.block, n=dims.n, n_pad=dims.n_pad, k=dims.k)
+        assert got == ref, w.name
+
+
+def test_derive_k_rule():
+    for (T, fh, fw, s) in [(33, 45, 80, 0.9), (5, 17, 23, 0.0), (5, 17, 23, 0.3), (7, 8, 8, 0.99), (3, 16, 16, 0.51)]:
+        p = da.problem(1, 1, T, fh, fw, 128, sparsity=s)
+        assert da.da_derive(p).k == oa.derive_dims(T, fh, fw, 8, 8, s)["k"]
+    p = da.problem(1, 1, 4, 16, 16, 128, keep_blocks=5)
+    assert da.da_derive(p).k == 5
+    p = da.problem(1, 1, 4, 16, 16, 128, keep_blocks=500)
+    assert da.da_derive(p).k == 16
+
+
+def _status(fn, *args):
+    with pytest.raises(da.DaError) as e:
+        fn(*args)
+    return e.value.status
+
+
+def test_bad_problems_are_rejected():
+    bad = [da.problem(0, 1, 1, 8, 8, 128), da.problem(1, 1, 1, 8, 8, 0), da.problem(1, 1, 1, 8, 8, 128, ph=0),
+           da.problem(1, 1, 1, 8, 8, 128, sparsity=1.0), da.problem(1, 1, 1, 8, 8, 128, sparsity=-0.1),
+           da.problem(1, 1, 1, 8, 8, 128, sparsity=float("nan")), da.problem(1, 1, 1, 8, 8, 128, dtype=7),
+           da.problem(1, 1, 1, 8, 8, 128, keep_blocks=-1), da.problem(1, 1, 100000, 4000, 4000, 128)]
+    for p in bad:
+        assert _status(da.da_derive, p) == -2
+        assert _status(da.da_workspace_size, p) == -2
+        assert _status(da.da_permute, p, FAKE, FAKE, da.DA_REORDER_ROWS, 0) == -2
+
+
+def test_null_alignment_mode_and_support_checks():
+    p = da.problem_of(W.CONFIGS["480p"])
+    assert _status(da.da_permute, p, None, FAKE, da.DA_REORDER_ROWS, 0) == -1
+    assert _status(da.da_permute, p, FAKE, FAKE + 4, da.DA_REORDER_ROWS, 0) == -5
+    assert _status(da.da_permute, p, FAKE, FAKE, 9, 0) == -2
+    assert _status(da.da_draft_map, p, FAKE, None, FAKE, FAKE, None, None, 0) == -1
+    assert _status(da.da_draft_map, p, FAKE, FAKE, None, FAKE, None, None, 0) == -1
+    assert _status(da.da_select_blocks, p, None, FAKE, None, 0) == -1
+    assert _status(da.da_select_blocks, p, FAKE, FAKE + 2, None, 0) == -5
+    assert _status(da.da_sparse_attn, p, FAKE, FAKE, FAKE, None, FAKE, None, 0) == -1
+    # unsupported shapes for the attention kernels: window not 64 slots, head dim, dtype/d pair
+    for q in (da.problem(1, 1, 2, 16, 16, 128, ph=8, pw=16), da.problem(1, 1, 2, 16, 16, 96),
+              da.problem(1, 1, 2, 16, 16, 64, dtype=da.DA_BF16), da.problem(1, 1, 2, 16, 16, 256, dtype=da.DA_F32)):
+        assert _status(da.da_sparse_attn, q, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0) == -3
+    # rows that are not a whole number of 16-byte chunks
+    q = da.problem(1, 1, 2, 16, 16, 12)
+    assert _status(da.da_permute, q, FAKE, FAKE, da.DA_REORDER_ROWS, 0) == -3
+    assert _status(da.da_draft_map, q, FAKE, FAKE, FAKE, FAKE, None, None, 0) == -3
+
+
+def test_forward_workspace_checks():
+    p = da.problem_of(W.CONFIGS["tiny_fp32"])
+    need = da.da_workspace_size(p)
+    assert need > 4 * 512 * 64 * 4 * 2
+    L = da.lib()
+    args = [ctypes.byref(p)] + [ctypes.c_void_p(FAKE)] * 4 + [None, ctypes.c_void_p(FAKE)]
+    assert L.da_forward(*args, ctypes.c_size_t(need - 1), None) == -4
+    assert L.da_forward(*args[:-1], ctypes.c_void_p(FAKE + 16), ctypes.c_size_t(need), None) == -5
+    assert L.da_forward(*args[:-1], None, ctypes.c_size_t(need), None) == -1
+    # the workspace of the headline configuration is a few GB, far below one GPU's HBM
+    big = da.da_workspace_size(da.problem_of(W.CONFIGS["720p_hunyuan"]))
+    assert 3.0e9 < big < 6.0e9
+
+
+def test_status_strings():
+    assert da.status_string(0) == "ok"
+    for s in range(-6, 0):
+        assert da.status_string(s) not in ("ok", "unknown status")
+    assert da.status_string(-99) == "unknown status"
