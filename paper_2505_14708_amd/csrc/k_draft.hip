@@ -9,6 +9,8 @@
 #include <math.h>
 #include "da_internal.h"
 
+// No fused multiply-add anywhere in this file: the pragma covers the code below, and the build
+// also passes -ffp-contract=off for this file.
 #pragma clang fp contract(off)
 
 namespace da {
@@ -59,7 +61,10 @@ __global__ __launch_bounds__(256) void draft_logits_kernel(Geo q, const float* _
 #pragma unroll
       for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[i][j] = __fadd_rn(acc[i][j], __fmul_rn(a[i], b[j]));
+        for (int j = 0; j < 8; ++j) {
+          float prod = a[i] * b[j];      // rounded on its own: this file is compiled with contraction off
+          acc[i][j] = acc[i][j] + prod;
+        }
     }
     __syncthreads();
   }
@@ -71,7 +76,7 @@ __global__ __launch_bounds__(256) void draft_logits_kernel(Geo q, const float* _
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       int c = col0 + (j < 4 ? tx * 4 + j : 64 + tx * 4 + (j - 4));
-      if (c < q.g) out[(long long)r * q.g + c] = __fmul_rn(acc[i][j], scale);
+      if (c < q.g) out[(long long)r * q.g + c] = acc[i][j] * scale;
     }
   }
 }

@@ -5,6 +5,8 @@
 // depend on the launch shape:  acc = acc + x (one rounding per add), mean = acc / valid.
 #include "da_internal.h"
 
+#pragma clang fp contract(off)
+
 namespace da {
 
 template <int DT>
@@ -61,20 +63,20 @@ __global__ __launch_bounds__(256) void pool_kernel(Geo q, const uint4* __restric
         float f[N];
         Vec<DT>::widen(r[t], f);
 #pragma unroll
-        for (int j = 0; j < N; ++j) acc[j] = __fadd_rn(acc[j], f[j]);
+        for (int j = 0; j < N; ++j) acc[j] = acc[j] + f[j];
       }
     }
     for (; v < b.vw; ++v) {
       float f[N];
       Vec<DT>::widen(row[(long long)v * cpr], f);
 #pragma unroll
-      for (int j = 0; j < N; ++j) acc[j] = __fadd_rn(acc[j], f[j]);
+      for (int j = 0; j < N; ++j) acc[j] = acc[j] + f[j];
     }
   }
   float cnt = (float)(b.vh * b.vw);
   float* dst = out + blk * q.d + c * N;
 #pragma unroll
-  for (int j = 0; j < N; ++j) dst[j] = __fdiv_rn(acc[j], cnt);
+  for (int j = 0; j < N; ++j) dst[j] = acc[j] / cnt;   // IEEE division (correctly rounded is the compiler default for HIP)
 }
 
 hipError_t launch_pool(const Geo& q, const void* Q, const void* K, float* q_pool, float* k_pool, hipStream_t s) {
