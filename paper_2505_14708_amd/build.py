@@ -30,6 +30,8 @@ STRICT_FP = {"k_pool.hip", "k_draft.hip"}
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
     extra = ["-ffp-contract=off"] if src in STRICT_FP else []
+    if src == "k_attn_bf16.hip":
+        extra.append("-fno-honor-nans")   # no NaN canonicalisation around max(); infinities stay exact
     cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"

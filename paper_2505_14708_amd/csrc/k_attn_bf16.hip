@@ -105,6 +105,27 @@ __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// Multiply an accumulator tile that lives in accumulation registers by a per-lane factor.
+// Written against the accumulation registers directly so that the (rare) rescale does not make
+// the compiler shuttle O between the two register files on every trip of the tile loop.
+__device__ __forceinline__ void scale_acc(f32x16& acc, float a) {
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    float x = acc[i], tmp;
+    asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\tv_accvgpr_write_b32 %0, %1"
+                 : "+a"(x), "=&v"(tmp)
+                 : "v"(a));
+    acc[i] = x;
+  }
+}
+// Tell the register allocator that an accumulator tile is wanted in accumulation registers here
+// (no instruction is emitted).
+__device__ __forceinline__ void pin_acc(f32x16& acc) { asm volatile("" : "+a"(acc)); }
+// wait states around scale_acc: matrix results must have been written before they are read, and
+// the rewritten registers must be visible to the next matrix instruction
+__device__ __forceinline__ void acc_hazard_before() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
+__device__ __forceinline__ void acc_hazard_after() { asm volatile("s_nop 7" ::: "memory"); }
+
 // ------------------------------------------------------------------------------------------
 // per-wave state and the pieces of one tile step
 // ------------------------------------------------------------------------------------------
@@ -192,10 +213,10 @@ __device__ __forceinline__ void tile_step(f32x16 (&sc)[2][2], f32x16 (&sn)[2][2]
         const float alpha = __builtin_amdgcn_exp2f((st.m[nt] - m_new) * kC2);   // exp2(-inf) = 0 the first time
         st.m[nt] = m_new;
         st.l[nt] *= alpha;
+        acc_hazard_before();
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) o[dt][nt][i] *= alpha;
+        for (int dt = 0; dt < 4; ++dt) scale_acc(o[dt][nt], alpha);
+        acc_hazard_after();
       }
     }
   }
@@ -366,8 +387,9 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(Geo q, const unsigned
   f32x16 sa[2][2], sb[2][2];
   int j0 = __builtin_amdgcn_readfirstlane(list[0]);
   int j1 = __builtin_amdgcn_readfirstlane(list[min(1, k - 1)]);
+  __builtin_amdgcn_s_waitcnt(0);                 // Q fragments in (builtin, so the compiler knows)
   dma_tile(Kbh + (long long)j0 * K_TILE, k_lds, koff);
-  wait_vm<0>();                                  // Q fragments and K(0)
+  wait_vm<0>();                                  // K(0)
   {
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
@@ -442,21 +464,441 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(Geo q, const unsigned
   }
 }
 
+
+// ==========================================================================================
+// Shared-tile kernel: the four wavefronts of a workgroup own four query blocks at the same
+// patch position in four consecutive frames.  Such blocks keep largely the same key blocks,
+// so the workgroup walks the UNION of their four lists once, in ascending order, and every
+// K/V tile of the union is brought into LDS once for all four (a ring of four 32 KB slots,
+// filled three tiles ahead by direct-to-LDS loads that the four waves share out).  A wave
+// computes on a tile only if its own list holds it.  One workgroup barrier per union tile
+// keeps the ring consistent: it separates "everyone is done with tile u-1" from the refill of
+// that slot, and "every share of tile u has landed" from its use.
+//
+// Inside a tile the 64 keys are taken as two online-softmax steps of 32 keys, so the vector
+// ALU work of one half (max, exp, sum, pack) can run under the matrix-core work of the other:
+//     S0 | S1 || softmax(S0) | PV0 || softmax(S1) | PV1
+// ==========================================================================================
+constexpr int RING = 4;
+constexpr int SLOT = K_TILE + V_TILE;             // 32 KB
+constexpr int RING_BYTES = RING * SLOT;           // 128 KB
+constexpr int LDS_TOTAL = 160 * 1024;
+constexpr int AUX_BYTES = LDS_TOTAL - RING_BYTES; // bitmaps + union list + counter
+
+struct Soft2 {
+  float m[2];     // reference max per query group (raw score units); -inf before the first tile
+  float l[2];     // this lane's partial sum of probabilities
+};
+
+// Scheduling hints.  The matrix pipe and the vector ALU of a SIMD work at the same time only if
+// the instruction stream of the (single) wave alternates between them, so the regions that
+// hold two independent streams are closed with a pattern "1 matrix instruction, then V vector
+// instructions", repeated; regions are fenced so that nothing drifts across.
+__device__ __forceinline__ void region_fence() { __builtin_amdgcn_sched_barrier(0); }
+template <int MFMAS, int VALU_PER>
+__device__ __forceinline__ void interleave_pattern() {
+#pragma unroll
+  for (int i = 0; i < MFMAS; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);          // one MFMA
+    __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER, 0);   // then VALU work
+  }
+}
+
+// value of the other half-wave's lane (l ^ 32) combined by max: one v_permlane32_swap
+__device__ __forceinline__ float max_across_halves(float x) {
+  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+  u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// row max of a 32-key half (two query groups) and the decision whether the reference max moves
+__device__ __forceinline__ bool half_max(const f32x16& s0, const f32x16& s1, const Soft2& st, float& mx0, float& mx1) {
+  mx0 = max_across_halves(max16(s0, -INFINITY));
+  mx1 = max_across_halves(max16(s1, -INFINITY));
+  // (mx - m) is NaN only when both are -inf (a half of pad keys before any real key): the
+  // comparison is then false and nothing moves.
+  return (mx0 - st.m[0]) * kC2 > kLazy || (mx1 - st.m[1]) * kC2 > kLazy;
+}
+
+// rare: move the reference max up and rescale what was accumulated against the old one
+__device__ __forceinline__ void move_reference(f32x16 (&o)[4][2], Soft2& st, float mx0, float mx1, float& a0,
+                                               float& a1) {
+  const float n0 = fmaxf(st.m[0], mx0), n1 = fmaxf(st.m[1], mx1);
+  a0 = st.m[0] == n0 ? 1.0f : __builtin_amdgcn_exp2f((st.m[0] - n0) * kC2);
+  a1 = st.m[1] == n1 ? 1.0f : __builtin_amdgcn_exp2f((st.m[1] - n1) * kC2);
+  st.m[0] = n0;
+  st.m[1] = n1;
+  st.l[0] *= a0;
+  st.l[1] *= a1;
+  acc_hazard_before();
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) {
+    scale_acc(o[dt][0], a0);
+    scale_acc(o[dt][1], a1);
+  }
+  acc_hazard_after();
+}
+
+// probabilities already packed for the matrix cores, brought to a new reference (rare path)
+__device__ __forceinline__ void scale_p(bf16x8& p, float a) {
+#pragma unroll
+  for (int i = 0; i < 8; i += 2) {
+    f32x2 v = {(float)p[i] * a, (float)p[i + 1] * a};
+    bf16x2 b = __builtin_convertvector(v, bf16x2);
+    p[i] = b[0];
+    p[i + 1] = b[1];
+  }
+}
+
+// pad keys of one 32-key half: accumulator register i of half mt is key 32mt + 16(i>>3) + 8hh + (i&7)
+__device__ __forceinline__ void mask_pad_half(f32x16& s0, f32x16& s1, int mt, int nv, int hh) {
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    int key = 32 * mt + 16 * (i >> 3) + 8 * hh + (i & 7);
+    if (key >= nv) {
+      s0[i] = -INFINITY;
+      s1[i] = -INFINITY;
+    }
+  }
+}
+
+// keep a score tile in ordinary vector registers (the softmax arithmetic reads it many times)
+__device__ __forceinline__ void pin_vgpr(f32x16& x) { asm volatile("" : "+v"(x)); }
+
+// One 64-key tile for one wave:  S0 | S1 || softmax(S0) | PV0 || softmax(S1) | PV1
+// Operands are read from LDS one region ahead of the matrix instructions that use them (an LDS
+// read takes on the order of a hundred cycles; requested just in time it would stall every
+// matrix instruction).
+__device__ __forceinline__ void compute_shared_tile(const unsigned char* kread, const unsigned char* vread, int ke,
+                                                    int ve, int hh, int nv, const bf16x8 (&qf)[2][8],
+                                                    f32x16 (&o)[4][2], Soft2& st) {
+  f32x16 s[2][2];
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  auto kfrag = [&](int mt, int t) { return *(const bf16x8*)(kread + mt * (32 * 256) + ((32 * t) ^ ke)); };
+  auto vfrag = [&](int t, int dt) { return *(const bf16x8*)(vread + dt * (32 * 128) + ((32 * t) ^ ve)); };
+  bf16x8 pf[2][4];
+  bf16x8 k0[8], k1[8], va[8], vb[8];
+  float mx0, mx1;
+  bool need;
+
+  // ---- region 1: all K operands requested; S0 = K[0..31] Q^T
+  region_fence();
+#pragma unroll
+  for (int t = 0; t < 8; ++t) k0[t] = kfrag(0, t);
+#pragma unroll
+  for (int t = 0; t < 8; ++t) k1[t] = kfrag(1, t);
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    s[0][0] = mfma(k0[t], qf[0][t], t == 0 ? zero : s[0][0]);
+    s[0][1] = mfma(k0[t], qf[1][t], t == 0 ? zero : s[0][1]);
+  }
+  __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
+  __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+  pin_vgpr(s[0][0]);
+  pin_vgpr(s[0][1]);
+  region_fence();
+  if (nv < BS) mask_pad_half(s[0][0], s[0][1], 0, nv, hh);
+
+  // ---- region 2: first quarter of S1 on the matrix cores, row max of S0 on the VALU
+  region_fence();
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    s[1][0] = mfma(k1[t], qf[0][t], t == 0 ? zero : s[1][0]);
+    s[1][1] = mfma(k1[t], qf[1][t], t == 0 ? zero : s[1][1]);
+  }
+  need = half_max(s[0][0], s[0][1], st, mx0, mx1);
+  interleave_pattern<4, 6>();
+  region_fence();
+  if (__any(need)) {
+    float a0, a1;
+    move_reference(o, st, mx0, mx1, a0, a1);
+  }
+
+  // ---- region 3: rest of S1 on the matrix cores, exp / sum / pack of S0 on the VALU;
+  //      the V operands of the first 32 keys are requested
+  region_fence();
+  {
+    float ls0 = 0.f, ls1 = 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) va[u] = vfrag(u >> 2, u & 3);
+#pragma unroll
+    for (int t = 2; t < 8; ++t) {
+      s[1][0] = mfma(k1[t], qf[0][t], s[1][0]);
+      s[1][1] = mfma(k1[t], qf[1][t], s[1][1]);
+    }
+    exp_pack(s[0][0], st.m[0] * kC2, ls0, pf[0][0], pf[0][1]);
+    exp_pack(s[0][1], st.m[1] * kC2, ls1, pf[1][0], pf[1][1]);
+    st.l[0] += ls0;
+    st.l[1] += ls1;
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+    interleave_pattern<12, 10>();
+  }
+  pin_vgpr(s[1][0]);
+  pin_vgpr(s[1][1]);
+  region_fence();
+  if (nv < BS) mask_pad_half(s[1][0], s[1][1], 1, nv, hh);
+
+  // ---- region 4: first quarter of PV0 on the matrix cores, row max of S1 on the VALU
+  region_fence();
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt) {
+    o[dt][0] = mfma(va[dt], pf[0][0], o[dt][0]);
+    o[dt][1] = mfma(va[dt], pf[1][0], o[dt][1]);
+  }
+  need = half_max(s[1][0], s[1][1], st, mx0, mx1);
+  interleave_pattern<4, 6>();
+  region_fence();
+  if (__any(need)) {
+    // Everything accumulated so far, the four products above included, was formed against the
+    // old reference and is rescaled; the probabilities of the first half still waiting in
+    // registers for the rest of PV0 are brought to the new reference as well.
+    float a0, a1;
+    move_reference(o, st, mx0, mx1, a0, a1);
+    scale_p(pf[0][0], a0);
+    scale_p(pf[0][1], a0);
+    scale_p(pf[1][0], a1);
+    scale_p(pf[1][1], a1);
+  }
+
+  // ---- region 5: rest of PV0 on the matrix cores, exp / sum / pack of S1 on the VALU;
+  //      the V operands of the last 32 keys are requested
+  region_fence();
+  {
+    float ls0 = 0.f, ls1 = 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) vb[u] = vfrag(2 + (u >> 2), u & 3);
+#pragma unroll
+    for (int dt = 2; dt < 4; ++dt) {
+      o[dt][0] = mfma(va[dt], pf[0][0], o[dt][0]);
+      o[dt][1] = mfma(va[dt], pf[1][0], o[dt][1]);
+    }
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+      o[dt][0] = mfma(va[4 + dt], pf[0][1], o[dt][0]);
+      o[dt][1] = mfma(va[4 + dt], pf[1][1], o[dt][1]);
+    }
+    exp_pack(s[1][0], st.m[0] * kC2, ls0, pf[0][2], pf[0][3]);
+    exp_pack(s[1][1], st.m[1] * kC2, ls1, pf[1][2], pf[1][3]);
+    st.l[0] += ls0;
+    st.l[1] += ls1;
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+    interleave_pattern<12, 10>();
+  }
+  region_fence();
+
+  // ---- region 6: PV1
+#pragma unroll
+  for (int t = 2; t < 4; ++t)
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+      o[dt][0] = mfma(vb[4 * (t - 2) + dt], pf[0][t], o[dt][0]);
+      o[dt][1] = mfma(vb[4 * (t - 2) + dt], pf[1][t], o[dt][1]);
+    }
+  region_fence();
+  // every operand of this tile was in registers before region 6: the slot can be refilled
+}
+
+__global__ __launch_bounds__(256, 1) void attn_bf16_shared_kernel(Geo q, const unsigned char* __restrict__ Qp,
+                                                                 const unsigned char* __restrict__ Kp,
+                                                                 const unsigned char* __restrict__ Vt,
+                                                                 const int32_t* __restrict__ idx,
+                                                                 unsigned char* __restrict__ Op,
+                                                                 float* __restrict__ lse, int dbg) {
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[LDS_TOTAL];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  // Heads one after the other; inside a head a workgroup is one patch position and four
+  // consecutive frames, and the frame groups of one position follow each other on one XCD
+  // (workgroups are dealt round-robin to the 8 XCDs).
+  const int per_frame = q.gh * q.gw;
+  const int fgs = (q.T + 3) >> 2;
+  const int pos_per_xcd = (per_frame + 7) >> 3;
+  const int wg_per_head = 8 * pos_per_xcd * fgs;
+  const long long bh = blockIdx.x / wg_per_head;
+  const int n = blockIdx.x - (int)(bh * wg_per_head);
+  const int xcd = n & 7, slot_id = n >> 3;
+  const int pos = xcd + 8 * (slot_id / fgs);
+  if (pos >= per_frame) return;                       // the whole workgroup leaves together
+  const int f = 4 * (slot_id % fgs) + wave;
+  const bool live = f < q.T;                          // a wave past the last frame only helps loading
+  const long long qb = bh * q.g + (long long)min(f, q.T - 1) * per_frame + pos;
+  const int k = q.k, g = q.g;
+
+  unsigned* bitmap = (unsigned*)(smem + RING_BYTES);  // [4][bw]
+  const int bw = (g + 31) >> 5;
+  unsigned* ulist = bitmap + 4 * bw;                  // entries: key block | membership << 24
+  unsigned* counter = (unsigned*)(smem + LDS_TOTAL - 16);
+
+  // ---- union of the four lists
+  for (int i = threadIdx.x; i < 4 * bw; i += 256) bitmap[i] = 0u;
+  __syncthreads();
+  if (live) {
+    const int32_t* list = idx + qb * k;
+    for (int e = lane; e < k; e += 64) {
+      int j = list[e];
+      atomicOr(&bitmap[wave * bw + (j >> 5)], 1u << (j & 31));
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    int cnt = 0;
+    for (int base = 0; base < g; base += 64) {
+      int j = base + lane;
+      unsigned m4 = 0;
+      if (j < g) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) m4 |= ((bitmap[w * bw + (j >> 5)] >> (j & 31)) & 1u) << w;
+      }
+      unsigned long long nz = __ballot(m4 != 0);
+      int before = __builtin_amdgcn_mbcnt_hi((unsigned)(nz >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)nz, 0));
+      if (m4) ulist[cnt + before] = (unsigned)j | (m4 << 24);
+      cnt += __popcll(nz);
+    }
+    if (lane == 0) *counter = (unsigned)cnt;
+  }
+  __syncthreads();
+  const int nU = __builtin_amdgcn_readfirstlane((int)*counter);
+
+  // ---- per-lane constants
+  const int r = lane & 31, hh = lane >> 5;
+  const int krow = sigma(r);
+  const int ke = (hh ^ (krow & 15)) << 4;
+  const int ve = (hh ^ ((r >> 1) & 7)) << 4;
+  const unsigned ring_lds = (unsigned)(uintptr_t)(lds_bytes)smem;
+  // this wave's share of a tile: steps it = wave, wave+4, wave+8, wave+12 of K and of V
+  unsigned koff, voff;
+  {
+    unsigned t4[4];
+    tile_lane_offsets<256>(lane, t4);
+    koff = wave == 0 ? t4[0] : wave == 1 ? t4[1] : wave == 2 ? t4[2] : t4[3];
+    tile_lane_offsets<128>(lane, t4);
+    voff = wave == 0 ? t4[0] : wave == 1 ? t4[1] : wave == 2 ? t4[2] : t4[3];
+  }
+  const unsigned char* Kbh = Kp + bh * q.n_pad * (D * 2);
+  const unsigned char* Vbh = Vt + bh * q.n_pad * (D * 2);
+  auto issue_share = [&](int u) {
+    const unsigned e = ulist[u];
+    const long long j = __builtin_amdgcn_readfirstlane((int)(e & 0xffffffu));
+    const unsigned dst = ring_lds + (unsigned)(u & (RING - 1)) * SLOT;
+    const unsigned char* ks = Kbh + j * K_TILE + koff;
+    const unsigned char* vs = Vbh + j * V_TILE + voff;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int it = wave + 4 * i;
+      dma16(ks + it * 1024, dst + it * 1024);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int it = wave + 4 * i;
+      dma16(vs + it * 1024, dst + K_TILE + it * 1024);
+    }
+  };
+
+  // Q fragments
+  bf16x8 qf[2][8];
+  {
+    const unsigned char* qbase = Qp + (qb * BS) * (D * 2);
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+      for (int t = 0; t < 8; ++t)
+        qf[nt][t] = *(const bf16x8*)(qbase + (32 * nt + r) * (D * 2) + (16 * t + 8 * hh) * 2);
+  }
+  f32x16 o[4][2];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[dt][nt][i] = 0.f;
+  Soft2 st;
+  st.m[0] = st.m[1] = -INFINITY;
+  st.l[0] = st.l[1] = 0.f;
+
+  // Wait for the Q fragments with the builtin (not inline assembly) so that the compiler's own
+  // counter bookkeeping knows they are in; otherwise it would wait for them again inside the
+  // loop and drain the tile prefetch with them.  From here only tile loads are in flight.
+  __builtin_amdgcn_s_waitcnt(0);
+#pragma unroll
+  for (int u = 0; u < RING - 1; ++u)
+    if (u < nU) issue_share(u);
+
+  const unsigned my_bit = live ? (1u << (24 + wave)) : 0u;
+  for (int u = 0; u < nU; ++u) {
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+      pin_acc(o[dt][0]);
+      pin_acc(o[dt][1]);
+    }
+    if (!(dbg & 2)) {
+      // my share of tile u has landed (shares of the up to two younger tiles may still fly)
+      if (u + 2 < nU) wait_vm<16>(); else if (u + 1 < nU) wait_vm<8>(); else wait_vm<0>();
+      __builtin_amdgcn_s_barrier();                     // all shares of tile u landed; everyone left tile u-1
+      if (u + RING - 1 < nU) issue_share(u + RING - 1); // refill the slot tile u-1 used
+    }
+    const unsigned e = __builtin_amdgcn_readfirstlane(ulist[u]);
+    if ((e & my_bit) && !(dbg & 1)) {
+      const int j = (int)(e & 0xffffffu);
+      const int nv = valid_slots(q, per_frame, j);
+      const unsigned char* slot = smem + (u & (RING - 1)) * SLOT;
+      compute_shared_tile(slot + krow * 256, slot + K_TILE + r * 128, ke, ve, hh, nv, qf, o, st);
+    }
+  }
+  if (dbg & 2) wait_vm<0>();
+  __builtin_amdgcn_s_barrier();                       // the ring is free: reuse it to stage the output
+  if (!live) return;
+
+  unsigned char* stage = smem + wave * SLOT;
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt) {
+    const float lt = st.l[nt] + __shfl_xor(st.l[nt], 32);
+    const float inv = 1.0f / lt;
+    if (lse && hh == 0) lse[qb * BS + 32 * nt + r] = st.m[nt] * kScale + __logf(lt);
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        f32x2 v0 = {o[dt][nt][4 * a] * inv, o[dt][nt][4 * a + 1] * inv};
+        f32x2 v1 = {o[dt][nt][4 * a + 2] * inv, o[dt][nt][4 * a + 3] * inv};
+        bf16x2 b0 = __builtin_convertvector(v0, bf16x2);
+        bf16x2 b1 = __builtin_convertvector(v1, bf16x2);
+        uint2 w2 = make_uint2(*(unsigned*)&b0, *(unsigned*)&b1);
+        *(uint2*)(stage + (32 * nt + r) * O_STRIDE + (32 * dt + 8 * a + 4 * hh) * 2) = w2;
+      }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  unsigned char* obase = Op + (qb * BS) * (D * 2);
+#pragma unroll
+  for (int it = 0; it < 16; ++it) {
+    int row = it * 4 + (lane >> 4), ch = lane & 15;
+    *(uint4*)(obase + row * (D * 2) + ch * 16) = *(const uint4*)(stage + row * O_STRIDE + ch * 16);
+  }
+}
+
 hipError_t launch_attn_bf16(const Geo& q, const void* Qp, const void* Kp, const void* Vt, const int32_t* idx, void* Op,
                             float* lse, hipStream_t s) {
+  const int per_frame = q.gh * q.gw;
+  // DA_ATTN_KERNEL=private selects the kernel in which every wave streams its own tiles (the
+  // fallback when the union bookkeeping of the shared-tile kernel does not fit in LDS).
+  const char* env = getenv("DA_ATTN_KERNEL");
+  bool want_private = env && strcmp(env, "private") == 0;
+  long long union_max = (long long)q.g < 4LL * q.k ? q.g : 4LL * q.k;
+  long long aux = 4LL * 4 * ((q.g + 31) / 32) + 4 * union_max + 64;
+  if (!want_private && aux <= AUX_BYTES && q.g < (1 << 24)) {
+    unsigned grid = (unsigned)((long long)q.B * q.H * 8 * ((per_frame + 7) / 8) * ((q.T + 3) / 4));
+    hipLaunchKernelGGL(attn_bf16_shared_kernel, dim3(grid), dim3(256), 0, s, q, (const unsigned char*)Qp,
+                       (const unsigned char*)Kp, (const unsigned char*)Vt, idx, (unsigned char*)Op, lse,
+                       getenv("DA_ATTN_DBG") ? atoi(getenv("DA_ATTN_DBG")) : 0);
+    return hipGetLastError();
+  }
   long long total_qb = (long long)q.B * q.H * q.g;
   long long wgs = (total_qb + 3) / 4;
   int wg_per_xcd = (int)((wgs + 7) / 8);
-  unsigned grid = (unsigned)(wg_per_xcd * 8);
-  const char* env = getenv("DA_ATTN_MAP");
-  int map_mode = env ? atoi(env) : 1;
-  if (map_mode != 0) {
-    int per_frame = q.gh * q.gw;
-    grid = (unsigned)((long long)q.B * q.H * 8 * ((per_frame + 7) / 8) * ((q.T + 3) / 4));
-  }
+  unsigned grid = (unsigned)((long long)q.B * q.H * 8 * ((per_frame + 7) / 8) * ((q.T + 3) / 4));
   hipLaunchKernelGGL(attn_bf16_kernel, dim3(grid), dim3(256), 0, s, q, (const unsigned char*)Qp,
                      (const unsigned char*)Kp, (const unsigned char*)Vt, idx, (unsigned char*)Op, lse, wg_per_xcd,
-                     total_qb, map_mode);
+                     total_qb, 1);
   return hipGetLastError();
 }
 
