@@ -569,34 +569,49 @@ __device__ __forceinline__ void pin_vgpr(f32x16& x) { asm volatile("" : "+v"(x))
 // Operands are read from LDS one region ahead of the matrix instructions that use them (an LDS
 // read takes on the order of a hundred cycles; requested just in time it would stall every
 // matrix instruction).
-__device__ __forceinline__ void compute_shared_tile(const unsigned char* kread, const unsigned char* vread, int ke,
-                                                    int ve, int hh, int nv, const bf16x8 (&qf)[2][8],
-                                                    f32x16 (&o)[4][2], Soft2& st) {
+struct TileOperands {
+  bf16x8 k0[8], k1[8];   // K rows of keys 0..31 / 32..63, one per k-step over d
+  bf16x8 va[8], vb[8];   // V^T rows: va = keys 0..31 (k-steps 0,1 x 4 channel groups), vb = keys 32..63
+};
+
+// All 32 operand reads of a tile are issued at once; the caller waits for them and can then
+// hand the LDS slot back long before the arithmetic on the tile is finished.
+__device__ __forceinline__ void fetch_tile_operands(TileOperands& x, const unsigned char* kread,
+                                                    const unsigned char* vread, int ke, int ve) {
+#pragma unroll
+  for (int t = 0; t < 8; ++t) x.k0[t] = *(const bf16x8*)(kread + ((32 * t) ^ ke));
+#pragma unroll
+  for (int t = 0; t < 8; ++t) x.k1[t] = *(const bf16x8*)(kread + 32 * 256 + ((32 * t) ^ ke));
+#pragma unroll
+  for (int u = 0; u < 8; ++u) x.va[u] = *(const bf16x8*)(vread + (u & 3) * (32 * 128) + ((32 * (u >> 2)) ^ ve));
+#pragma unroll
+  for (int u = 0; u < 8; ++u) x.vb[u] = *(const bf16x8*)(vread + (u & 3) * (32 * 128) + ((32 * (2 + (u >> 2))) ^ ve));
+}
+
+template <typename Mid>
+__device__ __forceinline__ void compute_shared_tile(const TileOperands& x, int hh, int nv, const bf16x8 (&qf)[2][8],
+                                                    f32x16 (&o)[4][2], Soft2& st, Mid&& mid) {
   f32x16 s[2][2];
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  auto kfrag = [&](int mt, int t) { return *(const bf16x8*)(kread + mt * (32 * 256) + ((32 * t) ^ ke)); };
-  auto vfrag = [&](int t, int dt) { return *(const bf16x8*)(vread + dt * (32 * 128) + ((32 * t) ^ ve)); };
   bf16x8 pf[2][4];
-  bf16x8 k0[8], k1[8], va[8], vb[8];
+  const bf16x8 (&k0)[8] = x.k0;
+  const bf16x8 (&k1)[8] = x.k1;
+  const bf16x8 (&va)[8] = x.va;
+  const bf16x8 (&vb)[8] = x.vb;
   float mx0, mx1;
   bool need;
 
-  // ---- region 1: all K operands requested; S0 = K[0..31] Q^T
+  // ---- region 1: S0 = K[0..31] Q^T
   region_fence();
-#pragma unroll
-  for (int t = 0; t < 8; ++t) k0[t] = kfrag(0, t);
-#pragma unroll
-  for (int t = 0; t < 8; ++t) k1[t] = kfrag(1, t);
 #pragma unroll
   for (int t = 0; t < 8; ++t) {
     s[0][0] = mfma(k0[t], qf[0][t], t == 0 ? zero : s[0][0]);
     s[0][1] = mfma(k0[t], qf[1][t], t == 0 ? zero : s[0][1]);
   }
-  __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
-  __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
   pin_vgpr(s[0][0]);
   pin_vgpr(s[0][1]);
   region_fence();
+  mid();           // a moment for ring housekeeping while the first scores drain from the matrix pipe
   if (nv < BS) mask_pad_half(s[0][0], s[0][1], 0, nv, hh);
 
   // ---- region 2: first quarter of S1 on the matrix cores, row max of S0 on the VALU
@@ -620,8 +635,6 @@ __device__ __forceinline__ void compute_shared_tile(const unsigned char* kread, 
   {
     float ls0 = 0.f, ls1 = 0.f;
 #pragma unroll
-    for (int u = 0; u < 8; ++u) va[u] = vfrag(u >> 2, u & 3);
-#pragma unroll
     for (int t = 2; t < 8; ++t) {
       s[1][0] = mfma(k1[t], qf[0][t], s[1][0]);
       s[1][1] = mfma(k1[t], qf[1][t], s[1][1]);
@@ -630,7 +643,6 @@ __device__ __forceinline__ void compute_shared_tile(const unsigned char* kread, 
     exp_pack(s[0][1], st.m[1] * kC2, ls1, pf[1][0], pf[1][1]);
     st.l[0] += ls0;
     st.l[1] += ls1;
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
     interleave_pattern<12, 10>();
   }
   pin_vgpr(s[1][0]);
@@ -666,8 +678,6 @@ __device__ __forceinline__ void compute_shared_tile(const unsigned char* kread, 
   {
     float ls0 = 0.f, ls1 = 0.f;
 #pragma unroll
-    for (int u = 0; u < 8; ++u) vb[u] = vfrag(2 + (u >> 2), u & 3);
-#pragma unroll
     for (int dt = 2; dt < 4; ++dt) {
       o[dt][0] = mfma(va[dt], pf[0][0], o[dt][0]);
       o[dt][1] = mfma(va[dt], pf[1][0], o[dt][1]);
@@ -681,7 +691,6 @@ __device__ __forceinline__ void compute_shared_tile(const unsigned char* kread, 
     exp_pack(s[1][1], st.m[1] * kC2, ls1, pf[1][2], pf[1][3]);
     st.l[0] += ls0;
     st.l[1] += ls1;
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
     interleave_pattern<12, 10>();
   }
   region_fence();
@@ -728,9 +737,21 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_shared_kernel(Geo q, const u
   const int bw = (g + 31) >> 5;
   unsigned* ulist = bitmap + 4 * bw;                  // entries: key block | membership << 24
   unsigned* counter = (unsigned*)(smem + LDS_TOTAL - 16);
+  int* ready = (int*)(smem + LDS_TOTAL - 64);         // [RING] union index whose tile the slot holds
+  unsigned* passed = (unsigned*)(smem + LDS_TOTAL - 48);   // [RING] how many waves have left the slot, ever
+  int* next_load = (int*)(smem + LDS_TOTAL - 32);     // next union entry nobody has requested yet
+  int* freed = (int*)(smem + LDS_TOTAL - 28);         // union entries every wave has left (they leave in order)
 
   // ---- union of the four lists
   for (int i = threadIdx.x; i < 4 * bw; i += 256) bitmap[i] = 0u;
+  if (threadIdx.x < RING) {
+    ready[threadIdx.x] = -1;
+    passed[threadIdx.x] = 0u;
+  }
+  if (threadIdx.x == 0) {
+    *next_load = 0;
+    *freed = 0;
+  }
   __syncthreads();
   if (live) {
     const int32_t* list = idx + qb * k;
@@ -765,32 +786,25 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_shared_kernel(Geo q, const u
   const int ke = (hh ^ (krow & 15)) << 4;
   const int ve = (hh ^ ((r >> 1) & 7)) << 4;
   const unsigned ring_lds = (unsigned)(uintptr_t)(lds_bytes)smem;
-  // this wave's share of a tile: steps it = wave, wave+4, wave+8, wave+12 of K and of V
-  unsigned koff, voff;
-  {
-    unsigned t4[4];
-    tile_lane_offsets<256>(lane, t4);
-    koff = wave == 0 ? t4[0] : wave == 1 ? t4[1] : wave == 2 ? t4[2] : t4[3];
-    tile_lane_offsets<128>(lane, t4);
-    voff = wave == 0 ? t4[0] : wave == 1 ? t4[1] : wave == 2 ? t4[2] : t4[3];
-  }
+  unsigned koff[4], voff[4];
+  tile_lane_offsets<256>(lane, koff);
+  tile_lane_offsets<128>(lane, voff);
   const unsigned char* Kbh = Kp + bh * q.n_pad * (D * 2);
   const unsigned char* Vbh = Vt + bh * q.n_pad * (D * 2);
-  auto issue_share = [&](int u) {
+  // one wave brings a whole tile (K and V^T of union entry u) into ring slot u % RING
+  auto issue_tile = [&](int u) {
     const unsigned e = ulist[u];
     const long long j = __builtin_amdgcn_readfirstlane((int)(e & 0xffffffu));
     const unsigned dst = ring_lds + (unsigned)(u & (RING - 1)) * SLOT;
-    const unsigned char* ks = Kbh + j * K_TILE + koff;
-    const unsigned char* vs = Vbh + j * V_TILE + voff;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int it = wave + 4 * i;
-      dma16(ks + it * 1024, dst + it * 1024);
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int it = wave + 4 * i;
-      dma16(vs + it * 1024, dst + K_TILE + it * 1024);
+    dma_tile(Kbh + j * K_TILE, dst, koff);
+    dma_tile(Vbh + j * V_TILE, dst + K_TILE, voff);
+  };
+  // a tile this wave has requested becomes visible to the others once it has landed
+  auto publish = [&](int& pending) {
+    if (pending >= 0) {
+      wait_vm<0>();
+      if (lane == 0) __atomic_store_n(&ready[pending & (RING - 1)], pending, __ATOMIC_RELAXED);
+      pending = -1;
     }
   };
 
@@ -819,33 +833,96 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_shared_kernel(Geo q, const u
   // counter bookkeeping knows they are in; otherwise it would wait for them again inside the
   // loop and drain the tile prefetch with them.  From here only tile loads are in flight.
   __builtin_amdgcn_s_waitcnt(0);
-#pragma unroll
-  for (int u = 0; u < RING - 1; ++u)
-    if (u < nU) issue_share(u);
-
+  // The ring is run without workgroup barriers.
+  //   ready[s]   union entry whose tile slot s holds (set once the tile has landed)
+  //   passed[s]  how many waves have ever left slot s; waves leave the entries in order, a wave
+  //              leaves an entry as soon as its operand reads are done (or at once if its list
+  //              does not hold the entry), and the wave that leaves last advances `freed`
+  //   next_load  entries are requested strictly in order, entry L as soon as L < freed + RING;
+  //              whichever wave notices first claims it with a compare-and-swap
+  // A wave that is waiting for a tile is the natural one to request tiles: it has nothing else
+  // to do, waits for the load to land and publishes it at once.  A busy wave only requests
+  // when it passes by and nobody else has; it publishes after the tile it is about to compute.
+  // Nobody can get more than RING entries ahead of the slowest wave, which keeps the counters
+  // of successive uses of a slot apart.  Every wait is bounded: if a tile does not show up the
+  // wave gives up (the output is then wrong, but the kernel always ends).
+  int pending = -1;
+  auto try_request = [&]() -> bool {
+    const int L = __builtin_amdgcn_readfirstlane(__atomic_load_n(next_load, __ATOMIC_RELAXED));
+    if (L >= nU) return false;
+    const int fr = __builtin_amdgcn_readfirstlane(__atomic_load_n(freed, __ATOMIC_RELAXED));
+    if (L >= fr + RING) return false;
+    int got = L + 1;
+    if (lane == 0) got = atomicCAS(next_load, L, L + 1);
+    got = __builtin_amdgcn_readfirstlane(got);
+    if (got != L) return false;
+    publish(pending);                                 // at most one request of mine is in flight
+    issue_tile(L);
+    pending = L;
+    return true;
+  };
   const unsigned my_bit = live ? (1u << (24 + wave)) : 0u;
-  for (int u = 0; u < nU; ++u) {
+  bool gave_up = false;
+  long long tc[6] = {0, 0, 0, 0, 0, 0};
+  long long t_prev = (dbg & 4) ? __builtin_readcyclecounter() : 0;
+#define TICK(c) if (dbg & 4) { long long t_now = __builtin_readcyclecounter(); tc[c] += t_now - t_prev; t_prev = t_now; }
+  for (int u = 0; u < nU && !gave_up; ++u) {
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) {
       pin_acc(o[dt][0]);
       pin_acc(o[dt][1]);
     }
+    const int slot_i = u & (RING - 1);
     if (!(dbg & 2)) {
-      // my share of tile u has landed (shares of the up to two younger tiles may still fly)
-      if (u + 2 < nU) wait_vm<16>(); else if (u + 1 < nU) wait_vm<8>(); else wait_vm<0>();
-      __builtin_amdgcn_s_barrier();                     // all shares of tile u landed; everyone left tile u-1
-      if (u + RING - 1 < nU) issue_share(u + RING - 1); // refill the slot tile u-1 used
+      try_request();
+      int spins = 0;
+      while (__builtin_amdgcn_readfirstlane(__atomic_load_n(&ready[slot_i], __ATOMIC_RELAXED)) != u) {
+        if (pending >= 0) {
+          long long t_a = (dbg & 4) ? __builtin_readcyclecounter() : 0;
+          publish(pending);                           // idle: wait for my own request and hand it over
+          if (dbg & 4) { tc[4] += __builtin_readcyclecounter() - t_a; tc[5] += 1; }
+        } else if (!try_request()) {
+          __builtin_amdgcn_s_sleep(2);
+          if (++spins > (1 << 20)) {
+            gave_up = true;
+            break;
+          }
+        }
+      }
+      if (gave_up) break;
     }
+    TICK(0)
     const unsigned e = __builtin_amdgcn_readfirstlane(ulist[u]);
-    if ((e & my_bit) && !(dbg & 1)) {
+    const bool mine = (e & my_bit) && !(dbg & 1);
+    TileOperands x;
+    if (mine) {
+      const unsigned char* slot = smem + slot_i * SLOT;
+      fetch_tile_operands(x, slot + krow * 256, slot + K_TILE + r * 128, ke, ve);
+    }
+    if (!(dbg & 2)) {
+      wait_lds();                                    // my reads of the slot are complete: hand it back
+      unsigned old = 0;
+      if (lane == 0) {
+        old = atomicAdd(&passed[slot_i], 1u);
+        if (old + 1 == 4u * (unsigned)((u >> 2) + 1)) __atomic_store_n(freed, u + 1, __ATOMIC_RELAXED);
+      }
+    }
+    TICK(1)
+    if (mine) {
       const int j = (int)(e & 0xffffffu);
       const int nv = valid_slots(q, per_frame, j);
-      const unsigned char* slot = smem + (u & (RING - 1)) * SLOT;
-      compute_shared_tile(slot + krow * 256, slot + K_TILE + r * 128, ke, ve, hh, nv, qf, o, st);
+      compute_shared_tile(x, hh, nv, qf, o, st, [&]() {
+        if (!(dbg & 2)) publish(pending);             // my request from the top of this trip has had time to land
+      });
+      TICK(2)
     }
   }
-  if (dbg & 2) wait_vm<0>();
-  __builtin_amdgcn_s_barrier();                       // the ring is free: reuse it to stage the output
+  publish(pending);
+  if ((dbg & 4) && lse && lane == 0) {
+    long long wid = (long long)blockIdx.x * 4 + wave;
+    for (int c = 0; c < 6; ++c) lse[wid * 6 + c] = (float)tc[c];
+  }
+  __syncthreads();                                    // everyone is done with the ring: reuse it to stage the output
   if (!live) return;
 
   unsigned char* stage = smem + wave * SLOT;
@@ -853,7 +930,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_shared_kernel(Geo q, const u
   for (int nt = 0; nt < 2; ++nt) {
     const float lt = st.l[nt] + __shfl_xor(st.l[nt], 32);
     const float inv = 1.0f / lt;
-    if (lse && hh == 0) lse[qb * BS + 32 * nt + r] = st.m[nt] * kScale + __logf(lt);
+    if (lse && hh == 0 && !(dbg & 4)) lse[qb * BS + 32 * nt + r] = st.m[nt] * kScale + __logf(lt);
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
