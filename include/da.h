@@ -131,9 +131,12 @@ int da_permute(const da_problem* p, const void* X, void* Y, int mode, void* stre
  * probability 0.  Op [B,H,n_pad,d] in the problem's dtype; rows of pad query slots are
  * written with unspecified finite values.  lse [B,H,n_pad] float (may be NULL) receives the
  * natural-log normaliser of each row.
- * Supported: block == 64 and (dtype, d) in {(DA_BF16, 128), (DA_BF16, 64), (DA_F32, 64),
- * (DA_F32, 128)}; anything else returns DA_ERR_UNSUPPORTED.  bf16 uses bf16 MFMA with
- * float32 accumulation and softmax; f32 uses float32 arithmetic throughout.
+ * Supported: block == 64 and (dtype, d) in {(DA_BF16, 128), (DA_F32, 64), (DA_F32, 128)};
+ * anything else returns DA_ERR_UNSUPPORTED.  bf16 uses bf16 MFMA with float32 accumulation and
+ * softmax (and bf16 probabilities); f32 uses float32 arithmetic throughout.  The bf16 kernel
+ * keeps the block lists of four query blocks in LDS, which bounds the problem: roughly
+ * g/2 + 4*min(g, 4k) bytes must fit in 32 KB (g up to about 7000 with nothing dropped, far
+ * more when k << g); larger problems return DA_ERR_UNSUPPORTED.
  */
 int da_sparse_attn(const da_problem* p, const void* Qp, const void* Kp, const void* Vt,
                    const int32_t* idx, void* Op, float* lse, void* stream);

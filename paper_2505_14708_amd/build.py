@@ -14,7 +14,7 @@ LIB_DIR = os.path.join(HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libdraftattn.so")
 
 SOURCES = ["da_api.hip", "k_permute.hip", "k_pool.hip", "k_draft.hip", "k_select.hip", "k_attn_f32.hip",
-           "k_attn_bf16.hip"]
+           "k_attn_bf16_ring.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -30,7 +30,11 @@ STRICT_FP = {"k_pool.hip", "k_draft.hip"}
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
     extra = ["-ffp-contract=off"] if src in STRICT_FP else []
-    if src == "k_attn_bf16.hip":
+    if src == "k_attn_bf16_ring.hip":
+        # all MFMA results in ordinary vector registers: the softmax reads the scores many times and
+        # a 32-query wave has the registers for it
+        extra += ["-mllvm", "-amdgpu-mfma-vgpr-form"]
+    if src == "k_attn_bf16_ring.hip":
         extra.append("-fno-honor-nans")   # no NaN canonicalisation around max(); infinities stay exact
     cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)

@@ -53,7 +53,7 @@ inline bool row_ok(const Geo& q) { return ((size_t)q.d * elem_size(q)) % 16 == 0
 
 inline bool attn_supported(const Geo& q) {
   if (q.block != 64) return false;
-  if (q.dtype == DA_BF16) return q.d == 128;
+  if (q.dtype == DA_BF16) return q.d == 128 && attn_bf16_ring_fits(q) != 0;
   return q.d == 64 || q.d == 128;
 }
 
@@ -168,7 +168,7 @@ int da_sparse_attn(const da_problem* p, const void* Qp, const void* Kp, const vo
     return DA_ERR_ALIGN;
   if (!attn_supported(q)) return DA_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
-  if (q.dtype == DA_BF16) return hip_status(launch_attn_bf16(q, Qp, Kp, Vt, idx, Op, lse, s));
+  if (q.dtype == DA_BF16) return hip_status(launch_attn_bf16_ring(q, Qp, Kp, Vt, idx, Op, lse, s));
   return hip_status(launch_attn_f32(q, (const float*)Qp, (const float*)Kp, (const float*)Vt, idx, (float*)Op, lse, s));
 }
 
@@ -206,7 +206,7 @@ int da_forward(const da_problem* p, const void* Q, const void* K, const void* V,
   if ((e = launch_permute(q, V, vt, DA_REORDER_VT, s)) != hipSuccess) return DA_ERR_HIP;
   // SparseAttn
   if (q.dtype == DA_BF16)
-    e = launch_attn_bf16(q, qp, kp, vt, idx, op, nullptr, s);
+    e = launch_attn_bf16_ring(q, qp, kp, vt, idx, op, nullptr, s);
   else
     e = launch_attn_f32(q, (const float*)qp, (const float*)kp, (const float*)vt, idx, (float*)op, nullptr, s);
   if (e != hipSuccess) return DA_ERR_HIP;

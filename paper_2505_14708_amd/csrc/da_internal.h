@@ -62,7 +62,9 @@ hipError_t launch_row_softmax(const Geo& q, const float* logits, float* draft, h
 hipError_t launch_select(const Geo& q, const float* scores, int32_t* idx, uint8_t* mask, hipStream_t s);
 hipError_t launch_attn_f32(const Geo& q, const float* Qp, const float* Kp, const float* Vt, const int32_t* idx,
                            float* Op, float* lse, hipStream_t s);
-hipError_t launch_attn_bf16(const Geo& q, const void* Qp, const void* Kp, const void* Vt, const int32_t* idx,
-                            void* Op, float* lse, hipStream_t s);
+// bf16 block-sparse attention (k_attn_bf16_ring.hip)
+int attn_bf16_ring_fits(const Geo& q);
+hipError_t launch_attn_bf16_ring(const Geo& q, const void* Qp, const void* Kp, const void* Vt, const int32_t* idx,
+                                 void* Op, float* lse, hipStream_t s);
 
 }  // namespace da

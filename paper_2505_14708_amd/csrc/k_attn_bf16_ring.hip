@@ -1,0 +1,537 @@
+// SparseAttn for bf16 storage, d = 128, 64-token blocks, on the CDNA4 matrix cores
+// (v_mfma_f32_32x32x16_bf16, float32 accumulation): the shared-ring kernel.
+//
+// Why tiles are shared.  With 64 queries against a 64-key tile the arithmetic intensity is
+// 64 flop per byte of K/V, far below the machine balance, and a kernel in which every query
+// block streams its own tiles is bound by the memory fabric.  Query blocks at the same patch
+// position in consecutive frames keep largely the same key blocks, so a workgroup takes four
+// such blocks and walks the UNION of their lists once: every K/V tile of the union is brought
+// into LDS once for all four.
+//
+// Workgroup = 8 wavefronts, two per SIMD.  A wavefront owns 32 queries (half a block): with
+// half the accumulators a wave fits in 256 registers, two waves share a SIMD, and while one is
+// in its softmax (vector ALU) the other keeps the matrix pipe busy; the same pairing hides LDS
+// latency and the waits of the ring protocol.  The two waves of a SIMD belong to different
+// query blocks so that they are rarely in the same phase.
+//
+// Per key tile a wave computes
+//     S^T = K Q^T      (64 keys x 32 queries: 2 MFMA tiles of 32x32, 8 k-steps over d)
+//     online softmax over the 64 keys
+//     O^T += V^T P^T   (128 channels x 32 queries: 4 MFMA tiles, 4 k-steps over the keys)
+// The transposed forms put the query on the lane axis (lane l holds query l%32), so row max and
+// row sum run down a lane's own registers plus one exchange between lanes l and l^32.  Lane l
+// feeds K row sigma(l%32) (sigma swaps bits 2 and 3): then the scores a lane holds in
+// accumulator registers 8t..8t+7 belong to keys 16t + 8*(l/32) + 0..7, exactly the eight
+// contraction elements the P^T operand of the second product needs, so P goes from accumulator
+// to operand without leaving the lane.  V arrives block-transposed from the reorder step, so
+// both K rows and V^T rows are read from LDS as plain 16-byte operands.
+//
+// The ring.  Four 32 KB slots (K tile + V^T tile).  Tiles travel HBM/L2 -> LDS by 16-byte
+// direct-to-LDS loads; the lane that writes LDS position p of row r fetches global chunk
+// p ^ swizzle(r), which makes the operand reads conflict-free.  There are no workgroup barriers
+// in the tile loop:
+//   ready[s]   union entry whose tile slot s holds (set once the tile has landed)
+//   passed[s]  how many waves have ever left slot s; every wave leaves the entries in order (at
+//              once if its list does not hold the entry), the wave that leaves last advances
+//              `freed`
+//   next_load  entries are requested strictly in order, entry L as soon as L < freed + 4;
+//              whichever wave notices first claims it with a compare-and-swap, preferably one
+//              that is waiting for a tile anyway: it waits for the load and publishes it at once.
+// Nobody gets more than four entries ahead of the slowest wave, which keeps the counters of
+// successive uses of a slot apart.  Every wait is bounded: if a tile does not show up the wave
+// gives up (its output is then wrong, but the kernel always ends).
+//
+// The running max only moves (and O is rescaled) when a row max exceeds it by more than 2^8 in
+// the exponent's units; until then probabilities are formed against the stale max, which is
+// exact after the final division because numerator and denominator share it.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#include "da_internal.h"
+
+namespace da {
+namespace ring {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) unsigned char* lds_bytes;
+
+constexpr int D = 128;
+constexpr int BS = 64;
+constexpr int K_TILE = BS * D * 2;   // 16 KB, rows of 256 B
+constexpr int V_TILE = D * BS * 2;   // 16 KB, rows of 128 B
+constexpr int RING = 4;
+constexpr int SLOT = K_TILE + V_TILE;
+constexpr int RING_BYTES = RING * SLOT;           // 128 KB
+constexpr int LDS_TOTAL = 160 * 1024;
+constexpr int AUX_BYTES = LDS_TOTAL - RING_BYTES; // bitmaps + union list + ring state
+constexpr int WAVES = 8;
+constexpr int O_STRIDE = D * 2 + 16;              // padded row stride of the output staging area
+constexpr float kScale = 0.08838834764831845f;                      // 1/sqrt(128)
+constexpr float kC2 = 0.08838834764831845f * 1.4426950408889634f;   // log2(e)/sqrt(128)
+constexpr float kLazy = 8.0f;                     // move the running max only past this many powers of two
+constexpr int kSpinLimit = 1 << 20;
+
+// ---------------------------------------------------------------------------------- tile movement
+// 16 KB tile, rows of ROWB bytes, moved 1 KB (64 lanes x 16 B) per step; step `it` covers rows
+// it*RPS .. it*RPS+RPS-1 (RPS*ROWB = 1024), so global and LDS offsets are both it*1024 plus a
+// per-lane part that only depends on it & 3.
+template <int ROWB>
+__device__ inline void tile_lane_offsets(int lane, unsigned loff[4]) {
+  constexpr int CPR = ROWB / 16;
+  constexpr int RPS = 64 / CPR;
+  const int r_in = lane / CPR, p = lane % CPR;
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+    int row = a * RPS + r_in;
+    int sw = ROWB == 256 ? (row & 15) : ((row >> 1) & 7);
+    loff[a] = r_in * ROWB + ((p ^ sw) << 4);
+  }
+}
+
+// Direct-to-LDS load of 16 bytes per lane: lane i's data lands at m0 + 16*i.
+__device__ __forceinline__ void dma16(const unsigned char* g, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory");
+}
+__device__ __forceinline__ void dma_tile(const unsigned char* src, unsigned lds_addr, const unsigned (&loff)[4]) {
+#pragma unroll
+  for (int it = 0; it < 16; ++it) dma16(src + it * 1024 + loff[it & 3], lds_addr + it * 1024);
+}
+__device__ __forceinline__ void wait_vm0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+__device__ inline int sigma(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
+
+__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// ---------------------------------------------------------------------------------- softmax pieces
+__device__ __forceinline__ float max16(const f32x16& a, float m) {
+#pragma unroll
+  for (int i = 0; i < 16; i += 2) m = fmaxf(fmaxf(a[i], a[i + 1]), m);   // v_max3_f32
+  return m;
+}
+
+// max with the other half-wave's lane (l ^ 32): one v_permlane32_swap
+__device__ __forceinline__ float max_across_halves(float x) {
+  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+  u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_across_halves(float x) {
+  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+  u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// exp / sum / pack of 16 scores (one accumulator tile) into two P operands
+__device__ __forceinline__ void exp_pack(const f32x16& s, float mc, float& lsum, bf16x8& p_lo, bf16x8& p_hi) {
+#pragma unroll
+  for (int i = 0; i < 16; i += 2) {
+    float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], kC2, -mc));
+    float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i + 1], kC2, -mc));
+    lsum += p0;
+    lsum += p1;
+    f32x2 pp = {p0, p1};
+    bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+    if (i < 8) {
+      p_lo[i] = pb[0];
+      p_lo[i + 1] = pb[1];
+    } else {
+      p_hi[i - 8] = pb[0];
+      p_hi[i - 7] = pb[1];
+    }
+  }
+}
+
+// pad keys out of the softmax: accumulator register i of half mt is key 32mt + 16(i>>3) + 8hh + (i&7)
+__device__ __forceinline__ void mask_pad_half(f32x16& s, int mt, int nv, int hh) {
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    int key = 32 * mt + 16 * (i >> 3) + 8 * hh + (i & 7);
+    if (key >= nv) s[i] = -INFINITY;
+  }
+}
+
+// Multiply an accumulator tile that lives in accumulation registers by a per-lane factor, written
+// against those registers directly so that the rare rescale does not make the compiler shuttle O
+// between the two register files on every trip of the tile loop.
+__device__ __forceinline__ void scale_acc(f32x16& acc, float a) {
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    float x = acc[i], tmp;
+    asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\tv_accvgpr_write_b32 %0, %1"
+                 : "+a"(x), "=&v"(tmp)
+                 : "v"(a));
+    acc[i] = x;
+  }
+}
+// wait states around scale_acc: matrix results must have been written before they are read, and
+// the rewritten registers must be visible to the next matrix instruction
+__device__ __forceinline__ void acc_hazard_before() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
+__device__ __forceinline__ void acc_hazard_after() { asm volatile("s_nop 7" ::: "memory"); }
+// tell the register allocator that an accumulator tile is wanted in accumulation registers here
+__device__ __forceinline__ void pin_acc(f32x16& acc) { asm volatile("" : "+a"(acc)); }
+
+__device__ __forceinline__ int valid_slots(const Geo& q, int per_frame, int j) {
+  int rr = j % per_frame;
+  int bi = rr / q.gw, bj = rr - bi * q.gw;
+  return min(q.ph, q.fh - bi * q.ph) * min(q.pw, q.fw - bj * q.pw);
+}
+
+struct Soft {
+  float m;     // reference max (raw score units); -inf before the first tile
+  float l;     // this lane's partial sum of probabilities
+};
+
+// One 64-key tile for one wave (32 queries).  kaddr[t] / vaddr[t] are this lane's LDS addresses
+// of the operand of k-step t (swizzle already applied); the other operands of a step sit at
+// fixed distances (second 32 keys: +8 KB; next 32 channels: +4 KB).
+__device__ __forceinline__ void compute_tile(const unsigned char* const (&kaddr)[8], const unsigned char* const (&vaddr)[4],
+                                             int hh, int nv, const bf16x8 (&qf)[8], f32x16 (&o)[4], Soft& st) {
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  f32x16 s0, s1;
+  // S^T = K Q^T
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    bf16x8 a0 = *(const bf16x8*)(kaddr[t]);
+    bf16x8 a1 = *(const bf16x8*)(kaddr[t] + 32 * 256);
+    s0 = mfma(a0, qf[t], t == 0 ? zero : s0);
+    s1 = mfma(a1, qf[t], t == 0 ? zero : s1);
+  }
+  if (nv < BS) {
+    mask_pad_half(s0, 0, nv, hh);
+    mask_pad_half(s1, 1, nv, hh);
+  }
+  // online softmax over the 64 keys
+  const float mx = max_across_halves(max16(s1, max16(s0, -INFINITY)));   // finite: slot 0 of a block is valid
+  if (__any((mx - st.m) * kC2 > kLazy)) {
+    const float m_new = fmaxf(st.m, mx);
+    const float alpha = st.m == m_new ? 1.0f : __builtin_amdgcn_exp2f((st.m - m_new) * kC2);   // 0 the first time
+    st.m = m_new;
+    st.l *= alpha;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[dt][i] *= alpha;
+  }
+  bf16x8 pf[4];
+  float ls = 0.f;
+  const float mc = st.m * kC2;
+  exp_pack(s0, mc, ls, pf[0], pf[1]);
+  exp_pack(s1, mc, ls, pf[2], pf[3]);
+  st.l += ls;
+  // O^T += V^T P^T
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+      bf16x8 a = *(const bf16x8*)(vaddr[t] + dt * (32 * 128));
+      o[dt] = mfma(a, pf[t], o[dt]);
+    }
+}
+
+__global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const unsigned char* __restrict__ Qp,
+                                                               const unsigned char* __restrict__ Kp,
+                                                               const unsigned char* __restrict__ Vt,
+                                                               const int32_t* __restrict__ idx,
+                                                               unsigned char* __restrict__ Op, float* __restrict__ lse,
+                                                               int balance) {
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[LDS_TOTAL];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  // Heads one after the other (the K/V of the heads in flight then fit the last-level cache);
+  // inside a head a workgroup is one patch position and four consecutive frames, and the frame
+  // groups of one position follow each other on one XCD (workgroups are dealt round-robin to the
+  // 8 XCDs).
+  const int per_frame = q.gh * q.gw;
+  const int fgs = (q.T + 3) >> 2;
+  const int pos_per_xcd = (per_frame + 7) >> 3;
+  const int wg_per_head = 8 * pos_per_xcd * fgs;
+  const long long bh = blockIdx.x / wg_per_head;
+  const int n = blockIdx.x - (int)(bh * wg_per_head);
+  const int xcd = n & 7, slot_id = n >> 3;
+  const int pos = xcd + 8 * (slot_id / fgs);
+  if (pos >= per_frame) return;                       // the whole workgroup leaves together
+  // waves w and w+4 share a SIMD: give them different query blocks
+  const int half = wave >> 2;
+  const int qblk = (wave + 2 * half) & 3;
+  const int f = 4 * (slot_id % fgs) + qblk;
+  const bool live = f < q.T;                          // a wave past the last frame only helps with the ring
+  const long long qb = bh * q.g + (long long)min(f, q.T - 1) * per_frame + pos;
+  const int k = q.k, g = q.g;
+
+  unsigned* bitmap = (unsigned*)(smem + RING_BYTES);  // [4][bw] one bitmap of kept key blocks per query block
+  const int bw = (g + 31) >> 5;
+  unsigned* ulist = bitmap + 4 * bw;                  // union entries: key block | (valid slots - 1) << 22 | membership << 28
+  const int union_max = min(g, 4 * k);
+  int* ready = (int*)(smem + LDS_TOTAL - 64);         // [RING]
+  unsigned* passed = (unsigned*)(smem + LDS_TOTAL - 48);   // [RING]
+  int* next_load = (int*)(smem + LDS_TOTAL - 32);
+  int* freed = (int*)(smem + LDS_TOTAL - 28);
+  int* count = (int*)(smem + LDS_TOTAL - 24);
+
+  // ---- union of the four lists
+  for (int i = threadIdx.x; i < 4 * bw; i += 512) bitmap[i] = 0u;
+  if (threadIdx.x < RING) {
+    ready[threadIdx.x] = -1;
+    passed[threadIdx.x] = 0u;
+  }
+  if (threadIdx.x == 0) {
+    *next_load = 0;
+    *freed = 0;
+  }
+  __syncthreads();
+  if (live && half == 0) {
+    const int32_t* list = idx + qb * k;
+    for (int e = lane; e < k; e += 64) {
+      int j = list[e];
+      atomicOr(&bitmap[qblk * bw + (j >> 5)], 1u << (j & 31));
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    int cnt = 0;
+    for (int base = 0; base < g; base += 64) {
+      int j = base + lane;
+      unsigned m4 = 0;
+      if (j < g) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) m4 |= ((bitmap[w * bw + (j >> 5)] >> (j & 31)) & 1u) << w;
+      }
+      unsigned long long nz = __ballot(m4 != 0);
+      int before = __builtin_amdgcn_mbcnt_hi((unsigned)(nz >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)nz, 0));
+      if (m4) ulist[cnt + before] = (unsigned)j | ((unsigned)(valid_slots(q, per_frame, j) - 1) << 22) | (m4 << 28);
+      cnt += __popcll(nz);
+    }
+    if (lane == 0) *count = cnt;
+  }
+  __syncthreads();
+  const int nU = __builtin_amdgcn_readfirstlane(*count);
+
+  // ---- order of the walk.  In ascending order the four blocks' shares of the work come in
+  // runs (the earliest frames of the union only matter to the first block, the latest only to
+  // the last), and since nobody can run more than RING entries ahead, waves would take turns
+  // waiting.  Entries with the same membership form a class (15 classes); each class is spread
+  // evenly over the walk: the p-th of c entries of a class gets the key (2p+1)/(2c), and the
+  // walk goes by ascending key.  Every stretch of the walk then holds every block's fair share.
+  // The softmax does not care about the order of the keys.  (Skipped when the two extra
+  // arrays it needs do not fit in LDS; the walk is then in ascending order.)
+  if (balance) {
+    unsigned* upos = ulist + union_max;               // position of an entry inside its class
+    int* ccount = (int*)(smem + LDS_TOTAL - 128);     // [16] entries per class
+    if (wave == 0) {
+      int cc = 0;                                     // lane m keeps the running count of class m
+      for (int base = 0; base < nU; base += 64) {
+        const int i = base + lane;
+        const unsigned m4 = i < nU ? ulist[i] >> 28 : 0u;
+        int mypos = 0;
+#pragma unroll
+        for (int m = 1; m < 16; ++m) {
+          unsigned long long b = __ballot(m4 == (unsigned)m);
+          int before = __builtin_amdgcn_mbcnt_hi((unsigned)(b >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)b, 0));
+          int have = __builtin_amdgcn_readlane(cc, m);
+          if (m4 == (unsigned)m) mypos = have + before;
+          if (lane == m) cc += __popcll(b);
+        }
+        if (i < nU) upos[i] = (unsigned)mypos;
+      }
+      if (lane < 16) ccount[lane] = lane == 0 ? 0 : cc;
+    }
+    __syncthreads();
+    unsigned* sorted = upos + union_max;
+    for (int i = threadIdx.x; i < nU; i += 512) {
+      const unsigned e = ulist[i];
+      const int m = (int)(e >> 28);
+      const int c = ccount[m];
+      const int a2 = 2 * (int)upos[i] + 1;            // my key is a2 / (2c)
+      int rank = 0;
+#pragma unroll
+      for (int m2 = 1; m2 < 16; ++m2) {
+        const int c2 = ccount[m2];
+        if (c2 == 0) continue;
+        // entries j of class m2 with (2j+1)/(2 c2) < a2/(2c), i.e. (2j+1) c < a2 c2
+        const int A = a2 * c2;
+        const int qq = (A + c - 1) / c;               // ceil(A / c)
+        int cntl = qq >> 1;
+        // an exact tie goes to the lower class number
+        if (m2 < m && A % c == 0 && ((A / c) & 1)) cntl += 1;
+        rank += min(cntl, c2);
+      }
+      sorted[rank] = e;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < nU; i += 512) ulist[i] = sorted[i];
+    __syncthreads();
+  }
+
+  // ---- per-lane constants
+  const int r = lane & 31, hh = lane >> 5;
+  const int krow = sigma(r);
+  const int ke = (hh ^ (krow & 15)) << 4;
+  const int ve = (hh ^ ((r >> 1) & 7)) << 4;
+  int kofs[8], vofs[4];                               // operand offsets inside a slot, swizzle applied
+#pragma unroll
+  for (int t = 0; t < 8; ++t) kofs[t] = krow * 256 + ((32 * t) ^ ke);
+#pragma unroll
+  for (int t = 0; t < 4; ++t) vofs[t] = K_TILE + r * 128 + ((32 * t) ^ ve);
+  const unsigned ring_lds = (unsigned)(uintptr_t)(lds_bytes)smem;
+  unsigned koff[4], voff[4];
+  tile_lane_offsets<256>(lane, koff);
+  tile_lane_offsets<128>(lane, voff);
+  const unsigned char* Kbh = Kp + bh * q.n_pad * (D * 2);
+  const unsigned char* Vbh = Vt + bh * q.n_pad * (D * 2);
+  // one wave brings a whole tile (K and V^T of union entry u) into ring slot u % RING
+  auto issue_tile = [&](int u) {
+    const unsigned e = ulist[u];
+    const long long j = __builtin_amdgcn_readfirstlane((int)(e & 0x3fffffu));
+    const unsigned dst = ring_lds + (unsigned)(u & (RING - 1)) * SLOT;
+    dma_tile(Kbh + j * K_TILE, dst, koff);
+    dma_tile(Vbh + j * V_TILE, dst + K_TILE, voff);
+  };
+  int pending = -1;
+  // a tile this wave has requested becomes visible to the others once it has landed
+  auto publish = [&]() {
+    if (pending >= 0) {
+      wait_vm0();
+      if (lane == 0) __atomic_store_n(&ready[pending & (RING - 1)], pending, __ATOMIC_RELAXED);
+      pending = -1;
+    }
+  };
+  auto try_request = [&]() -> bool {
+    const int L = __builtin_amdgcn_readfirstlane(__atomic_load_n(next_load, __ATOMIC_RELAXED));
+    if (L >= nU) return false;
+    const int fr = __builtin_amdgcn_readfirstlane(__atomic_load_n(freed, __ATOMIC_RELAXED));
+    if (L >= fr + RING) return false;
+    int got = L + 1;
+    if (lane == 0) got = atomicCAS(next_load, L, L + 1);
+    got = __builtin_amdgcn_readfirstlane(got);
+    if (got != L) return false;
+    publish();                                        // at most one request of mine is in flight
+    issue_tile(L);
+    pending = L;
+    return true;
+  };
+
+  // Q fragments: B operand, lane (query r, half-wave hh) holds d = 16t + 8hh .. +7
+  bf16x8 qf[8];
+  {
+    const unsigned char* qbase = Qp + (qb * BS + 32 * half) * (D * 2);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) qf[t] = *(const bf16x8*)(qbase + r * (D * 2) + (16 * t + 8 * hh) * 2);
+  }
+  f32x16 o[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
+  Soft st;
+  st.m = -INFINITY;
+  st.l = 0.f;
+  // Make the compiler wait for the Q fragments here, by touching them: its own counter
+  // bookkeeping then knows they are in.  Otherwise it would wait for them at their first use
+  // inside the tile loop, with a vmcnt that also drains the tile loads in flight.
+#pragma unroll
+  for (int t = 0; t < 8; ++t) asm volatile("" : "+v"(qf[t]));
+
+  const unsigned my_bit = live ? (1u << (28 + qblk)) : 0u;
+  bool gave_up = false;
+  for (int u = 0; u < nU && !gave_up; ++u) {
+    const int slot_i = u & (RING - 1);
+    {
+      try_request();
+      int spins = 0;
+      while (__builtin_amdgcn_readfirstlane(__atomic_load_n(&ready[slot_i], __ATOMIC_RELAXED)) != u) {
+        if (pending >= 0) {
+          publish();                                  // idle: wait for my own request and hand it over
+        } else if (!try_request()) {
+          __builtin_amdgcn_s_sleep(2);
+          if (++spins > kSpinLimit) {
+            gave_up = true;
+            break;
+          }
+        }
+      }
+      if (gave_up) break;
+    }
+    const unsigned e = __builtin_amdgcn_readfirstlane(ulist[u]);
+    if (e & my_bit) {
+      const int nv = (int)((e >> 22) & 63u) + 1;
+      const unsigned char* slot = smem + slot_i * SLOT;
+      const unsigned char* kaddr[8];
+      const unsigned char* vaddr[4];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) kaddr[t] = slot + kofs[t];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) vaddr[t] = slot + vofs[t];
+      compute_tile(kaddr, vaddr, hh, nv, qf, o, st);
+    }
+    {                                                 // my reads of the slot are complete: hand it back
+      wait_lds();
+      if (lane == 0) {
+        unsigned old = atomicAdd(&passed[slot_i], 1u);
+        if (old + 1 == (unsigned)WAVES * (unsigned)((u >> 2) + 1)) __atomic_store_n(freed, u + 1, __ATOMIC_RELAXED);
+      }
+    }
+    publish();
+  }
+  publish();
+  __syncthreads();                                    // everyone is done with the ring: reuse it to stage the output
+  if (!live) return;
+
+  // ---- epilogue: normalise, convert, stage through LDS, write rows of 256 B
+  unsigned char* stage = smem + wave * (RING_BYTES / WAVES);
+  {
+    const float lt = sum_across_halves(st.l);
+    const float inv = 1.0f / lt;
+    if (lse && hh == 0) lse[qb * BS + 32 * half + r] = st.m * kScale + __logf(lt);
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        // registers 4a..4a+3 are d = 32dt + 8a + 4hh + 0..3 of query r
+        f32x2 v0 = {o[dt][4 * a] * inv, o[dt][4 * a + 1] * inv};
+        f32x2 v1 = {o[dt][4 * a + 2] * inv, o[dt][4 * a + 3] * inv};
+        bf16x2 b0 = __builtin_convertvector(v0, bf16x2);
+        bf16x2 b1 = __builtin_convertvector(v1, bf16x2);
+        uint2 w2 = make_uint2(*(unsigned*)&b0, *(unsigned*)&b1);
+        *(uint2*)(stage + r * O_STRIDE + (32 * dt + 8 * a + 4 * hh) * 2) = w2;
+      }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  unsigned char* obase = Op + (qb * BS + 32 * half) * (D * 2);
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    int row = it * 4 + (lane >> 4), ch = lane & 15;
+    *(uint4*)(obase + row * (D * 2) + ch * 16) = *(const uint4*)(stage + row * O_STRIDE + ch * 16);
+  }
+}
+
+}  // namespace ring
+
+// LDS left beside the ring: four bitmaps of g bits, the union list (at most min(g, 4k) entries)
+// and, for the balanced walk, two more arrays of that length.
+// 0: the kernel cannot run this problem; 1: it can, walking in ascending order; 2: balanced walk.
+int attn_bf16_ring_fits(const Geo& q) {
+  if (q.g >= (1 << 22)) return 0;
+  long long union_max = (long long)q.g < 4LL * q.k ? q.g : 4LL * q.k;
+  long long base = 4LL * 4 * ((q.g + 31) / 32) + 4 * union_max + 256;
+  if (base > ring::AUX_BYTES) return 0;
+  return base + 8 * union_max <= ring::AUX_BYTES ? 2 : 1;
+}
+
+hipError_t launch_attn_bf16_ring(const Geo& q, const void* Qp, const void* Kp, const void* Vt, const int32_t* idx,
+                                 void* Op, float* lse, hipStream_t s) {
+  const int per_frame = q.gh * q.gw;
+  unsigned grid = (unsigned)((long long)q.B * q.H * 8 * ((per_frame + 7) / 8) * ((q.T + 3) / 4));
+  hipLaunchKernelGGL(ring::attn_bf16_ring_kernel, dim3(grid), dim3(512), 0, s, q, (const unsigned char*)Qp,
+                     (const unsigned char*)Kp, (const unsigned char*)Vt, idx, (unsigned char*)Op, lse,
+                     attn_bf16_ring_fits(q) == 2 ? 1 : 0);
+  return hipGetLastError();
+}
+
+}  // namespace da

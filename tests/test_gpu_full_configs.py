@@ -69,3 +69,30 @@ def test_full_config(name, heads, check):
         assert worst[0] <= tol_max and worst[1] <= tol_mean
     del ws, O, dQ, dK, dV
     torch.cuda.empty_cache()
+
+
+def test_many_blocks_ascending_walk():
+    """A problem whose union lists are too long for the balanced walk's extra arrays (the kernel
+    then walks in ascending order): 3000 one-patch frames, 800 key blocks kept per query block."""
+    import torch
+    w = W.Workload("many_blocks", B=1, H=1, d=128, T=3000, fh=8, fw=8, sparsity=0.0, seed=11)
+    say("many_blocks: generating")
+    Q, K, V = W.make_qkv(w)
+    p = da.problem(w.B, w.H, w.T, w.fh, w.fw, w.d, keep_blocks=800)
+    dims = da.da_derive(p)
+    assert dims.g == 3000 and dims.k == 800
+    ws = torch.empty(da.da_workspace_size(p), dtype=torch.uint8, device="cuda")
+    O = empty((1, 1, dims.n, w.d), w.dtype)
+    idx = torch.empty((1, 1, dims.g, dims.k), dtype=torch.int32, device="cuda")
+    da.da_forward(p, *(to_dev(x, w.dtype) for x in (Q, K, V)), O, ws, idx)
+    torch.cuda.synchronize()
+    say("many_blocks: GPU done")
+    ref = HeadRef(w, Q[0, 0], K[0, 0], V[0, 0], keep_blocks=800)
+    assert np.array_equal(idx.cpu().numpy()[0, 0], ref.idx)
+    rows = [0, 1, 2, 3, 1499, 2996, 2997, 2998, 2999]
+    want = ref.attention(rows=rows)
+    got = to_host_f64(O[0, 0], w.dtype)
+    for r in rows:
+        slots = np.arange(r * 64, (r + 1) * 64)
+        emax, emean = output_error(got[ref.perm[slots]], want[slots])
+        assert emax <= 2e-2 and emean <= 2e-3, (r, emax, emean)

@@ -4,8 +4,6 @@ outputs must be within the stated tolerances (bf16: max-abs 2e-2, mean-abs 2e-3;
 
 Sizes here finish in seconds on the oracle yet span several tiles and ragged tails:
 partial edge blocks of 48 / 40 / 32 / 24 valid slots, g not a multiple of any tile size."""
-import os
-
 import numpy as np
 import pytest
 
@@ -277,21 +275,18 @@ def test_sparse_attn_list_order_and_dense_case(torch_mod, cases):
     assert emax <= 2e-2 and emean <= 2e-3
 
 
-def test_sparse_attn_staged_variant_matches(torch_mod, cases):
-    """The register-staged tile loader builds the same LDS image as the direct-to-LDS one."""
+def test_sparse_attn_deterministic(torch_mod, cases):
+    """Two launches give the same bits (the ring's request order varies from run to run, the
+    arithmetic of a query block does not)."""
     torch = torch_mod
     w, Q, K, V, refs = cases["bf16_720p_T2"]
-    say("sparse_attn staged variant")
+    say("sparse_attn determinism")
     idx_np = np.stack([np.stack([refs[(b, h)].idx for h in range(w.H)]) for b in range(w.B)])
     p, dims, Qp, Kp, Vt, idx = _attn_inputs(torch, w, Q, K, V, refs, idx_np)
     O1 = empty((w.B, w.H, dims.n_pad, w.d), w.dtype)
     O2 = empty((w.B, w.H, dims.n_pad, w.d), w.dtype)
     da.da_sparse_attn(p, Qp, Kp, Vt, idx, O1, None)
-    os.environ["DA_ATTN_STAGED"] = "1"
-    try:
-        da.da_sparse_attn(p, Qp, Kp, Vt, idx, O2, None)
-    finally:
-        del os.environ["DA_ATTN_STAGED"]
+    da.da_sparse_attn(p, Qp, Kp, Vt, idx, O2, None)
     torch.cuda.synchronize()
     assert torch.equal(O1.view(torch.int16), O2.view(torch.int16))
 

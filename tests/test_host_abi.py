@@ -80,6 +80,9 @@ def test_null_alignment_mode_and_support_checks():
     for q in (da.problem(1, 1, 2, 16, 16, 128, ph=8, pw=16), da.problem(1, 1, 2, 16, 16, 96),
               da.problem(1, 1, 2, 16, 16, 64, dtype=da.DA_BF16), da.problem(1, 1, 2, 16, 16, 256, dtype=da.DA_F32)):
         assert _status(da.da_sparse_attn, q, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0) == -3
+    # bf16 attention keeps per-workgroup block lists in LDS: more than ~7000 blocks with nothing dropped do not fit
+    q = da.problem(1, 1, 8000, 8, 8, 128)
+    assert _status(da.da_sparse_attn, q, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0) == -3
     # rows that are not a whole number of 16-byte chunks
     q = da.problem(1, 1, 2, 16, 16, 12)
     assert _status(da.da_permute, q, FAKE, FAKE, da.DA_REORDER_ROWS, 0) == -3
