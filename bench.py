@@ -32,6 +32,10 @@ from paper_2505_14708_amd import workloads as W  # noqa: E402
 METRIC = "sparse-attn ms/layer + effective MFMA TFLOP/s @118.8k tokens, 90% sparsity"
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
+# HBM-side bytes per launch of the attention kernel (read, written), from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs of this program, scaled by what the same counters read for the row-copy kernel of known
+# size in the same run (profiles/pmc_traffic_720p_hunyuan.txt).  Workloads without a counter run: null.
+ATTN_TRAFFIC_BYTES = {"720p_hunyuan": (104.77e9, 0.779e9)}
 
 
 def cpu_baseline(w, Q, K, V, budget_s=20.0):
@@ -169,9 +173,11 @@ def main():
         "dtype": "f32" if w.dtype == W.F32 else "bf16", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "d": w.d, "T": w.T, "frame": [w.fh, w.fw], "N": w.N,
                    "pool": [w.ph, w.pw], "sparsity": w.sparsity, "g": g, "k": k, "n_pad": int(dims.n_pad)},
-        "roofline": {"kernel": "attn_bf16_kernel (da_sparse_attn)", "bound": "mfma",
+        "roofline": {"kernel": "da::ring::attn_bf16_ring_kernel (da_sparse_attn)", "bound": "mfma",
                      "achieved": eff_flop / (attn_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": eff_flop / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": eff_flop / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                     "traffic": (sum(ATTN_TRAFFIC_BYTES[w.name]) if w.name in ATTN_TRAFFIC_BYTES else None),
+                     "traffic_unit": "bytes per launch (read + written)",
                      "launch_ms": attn_ms, "flop_per_launch": eff_flop},
         "stages_ms": stage_ms,
         "hbm_stages": {"reorder_qkv_GBs": reorder_bytes / (stage_ms["reorder_qkv"] * 1e-3) / 1e9,

@@ -10,7 +10,7 @@ import ctypes
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("DA_LIB_PATH") or os.path.join(HERE, "lib", "libdraftattn.so")
+LIB_PATH = os.path.join(HERE, "lib", "libdraftattn.so")
 
 DA_F32, DA_BF16 = 0, 1
 DA_REORDER_ROWS, DA_REORDER_VT, DA_RESTORE = 0, 1, 2

@@ -156,26 +156,6 @@ __device__ __forceinline__ void mask_pad_half(f32x16& s, int mt, int nv, int hh)
   }
 }
 
-// Multiply an accumulator tile that lives in accumulation registers by a per-lane factor, written
-// against those registers directly so that the rare rescale does not make the compiler shuttle O
-// between the two register files on every trip of the tile loop.
-__device__ __forceinline__ void scale_acc(f32x16& acc, float a) {
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    float x = acc[i], tmp;
-    asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\tv_accvgpr_write_b32 %0, %1"
-                 : "+a"(x), "=&v"(tmp)
-                 : "v"(a));
-    acc[i] = x;
-  }
-}
-// wait states around scale_acc: matrix results must have been written before they are read, and
-// the rewritten registers must be visible to the next matrix instruction
-__device__ __forceinline__ void acc_hazard_before() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
-__device__ __forceinline__ void acc_hazard_after() { asm volatile("s_nop 7" ::: "memory"); }
-// tell the register allocator that an accumulator tile is wanted in accumulation registers here
-__device__ __forceinline__ void pin_acc(f32x16& acc) { asm volatile("" : "+a"(acc)); }
-
 __device__ __forceinline__ int valid_slots(const Geo& q, int per_frame, int j) {
   int rr = j % per_frame;
   int bi = rr / q.gw, bj = rr - bi * q.gw;
