@@ -72,6 +72,7 @@ constexpr int O_STRIDE = D * 2 + 16;              // padded row stride of the ou
 constexpr float kScale = 0.08838834764831845f;                      // 1/sqrt(128)
 constexpr float kC2 = 0.08838834764831845f * 1.4426950408889634f;   // log2(e)/sqrt(128)
 constexpr float kLazy = 8.0f;                     // move the running max only past this many powers of two
+constexpr float kSkip = 30.0f;                    // tiles whose probabilities all stay below 2^-kSkip are dropped
 constexpr int kSpinLimit = 1 << 20;
 
 // ---------------------------------------------------------------------------------- tile movement
@@ -164,6 +165,7 @@ __device__ __forceinline__ int valid_slots(const Geo& q, int per_frame, int j) {
 
 struct Soft {
   float m;     // reference max (raw score units); -inf before the first tile
+  float top;   // largest score seen so far (the reference trails it by at most kLazy powers of two)
   float l;     // this lane's partial sum of probabilities
 };
 
@@ -188,6 +190,13 @@ __device__ __forceinline__ void compute_tile(const unsigned char* const (&kaddr)
   }
   // online softmax over the 64 keys
   const float mx = max_across_halves(max16(s1, max16(s0, -INFINITY)));   // finite: slot 0 of a block is valid
+  // A key whose score is more than kSkip powers of two below the query's best score so far
+  // weighs less than 2^-kSkip of that query's largest term, in the normaliser and in the output:
+  // far below the resolution of the result for any sequence length this kernel accepts.  When
+  // that holds for every key of the tile and all 32 queries, the exponentials and the second
+  // product are skipped.  (Never the first time: top is -inf.)
+  if (__all((mx - st.top) * kC2 < -kSkip)) return;
+  st.top = fmaxf(st.top, mx);
   if (__any((mx - st.m) * kC2 > kLazy)) {
     const float m_new = fmaxf(st.m, mx);
     const float alpha = st.m == m_new ? 1.0f : __builtin_amdgcn_exp2f((st.m - m_new) * kC2);   // 0 the first time
@@ -273,12 +282,31 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
     }
   }
   __syncthreads();
+  // The workgroup's own four blocks go first (when kept): a query's best scores tend to be
+  // there, and the sooner the running maximum is near its final value, the more of the other
+  // tiles turn out negligible.
+  const int own_lo = (4 * (slot_id % fgs)) * per_frame + pos;   // own blocks: own_lo + w * per_frame, w = 0..3
   if (wave == 0) {
     int cnt = 0;
+    {
+      const int j = own_lo + lane * per_frame;
+      unsigned m4 = 0;
+      if (lane < 4 && j < g) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) m4 |= ((bitmap[w * bw + (j >> 5)] >> (j & 31)) & 1u) << w;
+      }
+      unsigned long long nz = __ballot(m4 != 0);
+      int before = __builtin_amdgcn_mbcnt_hi((unsigned)(nz >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)nz, 0));
+      if (m4) ulist[before] = (unsigned)j | ((unsigned)(valid_slots(q, per_frame, j) - 1) << 22) | (m4 << 28);
+      cnt = __popcll(nz);
+    }
+    const int n_own = cnt;
     for (int base = 0; base < g; base += 64) {
       int j = base + lane;
       unsigned m4 = 0;
-      if (j < g) {
+      const int dj = j - own_lo;
+      const bool own = dj >= 0 && dj < 4 * per_frame && dj % per_frame == 0;
+      if (j < g && !own) {
 #pragma unroll
         for (int w = 0; w < 4; ++w) m4 |= ((bitmap[w * bw + (j >> 5)] >> (j & 31)) & 1u) << w;
       }
@@ -287,10 +315,14 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
       if (m4) ulist[cnt + before] = (unsigned)j | ((unsigned)(valid_slots(q, per_frame, j) - 1) << 22) | (m4 << 28);
       cnt += __popcll(nz);
     }
-    if (lane == 0) *count = cnt;
+    if (lane == 0) {
+      count[0] = cnt;
+      count[1] = n_own;
+    }
   }
   __syncthreads();
-  const int nU = __builtin_amdgcn_readfirstlane(*count);
+  const int nU = __builtin_amdgcn_readfirstlane(count[0]);
+  const int n_own = __builtin_amdgcn_readfirstlane(count[1]);
 
   // ---- order of the walk.  In ascending order the four blocks' shares of the work come in
   // runs (the earliest frames of the union only matter to the first block, the latest only to
@@ -301,13 +333,15 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   // The softmax does not care about the order of the keys.  (Skipped when the two extra
   // arrays it needs do not fit in LDS; the walk is then in ascending order.)
   if (balance) {
+    unsigned* rest = ulist + n_own;                   // the own blocks keep their place in front
+    const int nR = nU - n_own;
     unsigned* upos = ulist + union_max;               // position of an entry inside its class
     int* ccount = (int*)(smem + LDS_TOTAL - 128);     // [16] entries per class
     if (wave == 0) {
       int cc = 0;                                     // lane m keeps the running count of class m
-      for (int base = 0; base < nU; base += 64) {
+      for (int base = 0; base < nR; base += 64) {
         const int i = base + lane;
-        const unsigned m4 = i < nU ? ulist[i] >> 28 : 0u;
+        const unsigned m4 = i < nR ? rest[i] >> 28 : 0u;
         int mypos = 0;
 #pragma unroll
         for (int m = 1; m < 16; ++m) {
@@ -317,14 +351,14 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
           if (m4 == (unsigned)m) mypos = have + before;
           if (lane == m) cc += __popcll(b);
         }
-        if (i < nU) upos[i] = (unsigned)mypos;
+        if (i < nR) upos[i] = (unsigned)mypos;
       }
       if (lane < 16) ccount[lane] = lane == 0 ? 0 : cc;
     }
     __syncthreads();
     unsigned* sorted = upos + union_max;
-    for (int i = threadIdx.x; i < nU; i += 512) {
-      const unsigned e = ulist[i];
+    for (int i = threadIdx.x; i < nR; i += 512) {
+      const unsigned e = rest[i];
       const int m = (int)(e >> 28);
       const int c = ccount[m];
       const int a2 = 2 * (int)upos[i] + 1;            // my key is a2 / (2c)
@@ -344,7 +378,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
       sorted[rank] = e;
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < nU; i += 512) ulist[i] = sorted[i];
+    for (int i = threadIdx.x; i < nR; i += 512) rest[i] = sorted[i];
     __syncthreads();
   }
 
@@ -410,6 +444,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
     for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
   Soft st;
   st.m = -INFINITY;
+  st.top = -INFINITY;
   st.l = 0.f;
   // Make the compiler wait for the Q fragments here, by touching them: its own counter
   // bookkeeping then knows they are in.  Otherwise it would wait for them at their first use
