@@ -5,8 +5,8 @@
 // 64 flop per byte of K/V, far below the machine balance, and a kernel in which every query
 // block streams its own tiles is bound by the memory fabric.  Query blocks at the same patch
 // position in consecutive frames keep largely the same key blocks, so a workgroup takes four
-// such blocks and walks the UNION of their lists once: every K/V tile of the union is brought
-// into LDS once for all four.
+// such blocks and walks the UNION of their lists once: every K tile of the union is brought
+// into LDS once for all four, and the V tiles they fetch meet in L2.
 //
 // Workgroup = 8 wavefronts, two per SIMD.  A wavefront owns 32 queries (half a block): with
 // half the accumulators a wave fits in 256 registers, two waves share a SIMD, and while one is
@@ -26,20 +26,25 @@
 // to operand without leaving the lane.  V arrives block-transposed from the reorder step, so
 // both K rows and V^T rows are read from LDS as plain 16-byte operands.
 //
-// The ring.  Four 32 KB slots (K tile + V^T tile).  Tiles travel HBM/L2 -> LDS by 16-byte
+// The ring.  Eight 16 KB slots, each one K tile.  Tiles travel HBM/L2 -> LDS by 16-byte
 // direct-to-LDS loads; the lane that writes LDS position p of row r fetches global chunk
 // p ^ swizzle(r), which makes the operand reads conflict-free.  There are no workgroup barriers
 // in the tile loop:
-//   ready[s]   union entry whose tile slot s holds (set once the tile has landed)
-//   passed[s]  how many waves have ever left slot s; every wave leaves the entries in order (at
-//              once if its list does not hold the entry), the wave that leaves last advances
-//              `freed`
-//   next_load  entries are requested strictly in order, entry L as soon as L < freed + 4;
-//              whichever wave notices first claims it with a compare-and-swap, preferably one
-//              that is waiting for a tile anyway: it waits for the load and publishes it at once.
-// Nobody gets more than four entries ahead of the slowest wave, which keeps the counters of
-// successive uses of a slot apart.  Every wait is bounded: if a tile does not show up the wave
-// gives up (its output is then wrong, but the kernel always ends).
+//   ready[s]   union entry whose K tile slot s holds (set once the tile has landed)
+//   prog[w]    how many entries wave w has left behind (it leaves them in order, at once if its
+//              list does not hold the entry); the slowest wave bounds what may be overwritten
+//   next_load  entries are requested strictly in order, entry L as soon as L < min(prog) + 8;
+//              whichever wave notices first claims it with a compare-and-swap, waits for the load
+//              at the top of its next trip (or while it is idle) and publishes it.
+// A wave reads all of this with one LDS access per poll.  Every wait is bounded: if a tile does
+// not show up the wave gives up (its output is then wrong, but the kernel always ends).
+//
+// V does not go through LDS.  After S = QK^T of a tile a wave knows the largest score of each of
+// its queries; when every score of the tile is more than 30 powers of two below the best the
+// query has seen, the tile cannot change the result at the precision of the output and its
+// exponentials and second product are skipped.  With peaked attention that is the common case,
+// so V^T operands are fetched from global memory (L2) straight into registers, only by the waves
+// that need them, while the exponentials are being computed.
 //
 // The running max only moves (and O is rescaled) when a row max exceeds it by more than 2^8 in
 // the exponent's units; until then probabilities are formed against the stale max, which is
@@ -62,8 +67,8 @@ constexpr int D = 128;
 constexpr int BS = 64;
 constexpr int K_TILE = BS * D * 2;   // 16 KB, rows of 256 B
 constexpr int V_TILE = D * BS * 2;   // 16 KB, rows of 128 B
-constexpr int RING = 4;
-constexpr int SLOT = K_TILE + V_TILE;
+constexpr int RING = 8;
+constexpr int SLOT = K_TILE;
 constexpr int RING_BYTES = RING * SLOT;           // 128 KB
 constexpr int LDS_TOTAL = 160 * 1024;
 constexpr int AUX_BYTES = LDS_TOTAL - RING_BYTES; // bitmaps + union list + ring state
@@ -169,11 +174,12 @@ struct Soft {
   float l;     // this lane's partial sum of probabilities
 };
 
-// One 64-key tile for one wave (32 queries).  kaddr[t] / vaddr[t] are this lane's LDS addresses
-// of the operand of k-step t (swizzle already applied); the other operands of a step sit at
-// fixed distances (second 32 keys: +8 KB; next 32 channels: +4 KB).
-__device__ __forceinline__ void compute_tile(const unsigned char* const (&kaddr)[8], const unsigned char* const (&vaddr)[4],
-                                             int hh, int nv, const bf16x8 (&qf)[8], f32x16 (&o)[4], Soft& st) {
+// One 64-key tile for one wave (32 queries).  kaddr[t] is this lane's LDS address of the K
+// operand of k-step t (swizzle already applied; the second 32 keys sit 8 KB further).  vt is
+// this lane's part of the tile's V^T in global memory: channel row r, 16-byte chunk hh; the
+// operand of (k-step t, channel group dt) is 32t bytes and 32dt rows further.
+__device__ __forceinline__ void compute_tile(const unsigned char* const (&kaddr)[8], const unsigned char* vt, int hh,
+                                             int nv, bool pad_query, const bf16x8 (&qf)[8], f32x16 (&o)[4], Soft& st) {
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   f32x16 s0, s1;
   // S^T = K Q^T
@@ -194,8 +200,15 @@ __device__ __forceinline__ void compute_tile(const unsigned char* const (&kaddr)
   // weighs less than 2^-kSkip of that query's largest term, in the normaliser and in the output:
   // far below the resolution of the result for any sequence length this kernel accepts.  When
   // that holds for every key of the tile and all 32 queries, the exponentials and the second
-  // product are skipped.  (Never the first time: top is -inf.)
-  if (__all((mx - st.top) * kC2 < -kSkip)) return;
+  // product are skipped.  (Never the first time: top is -inf.)  Pad query slots have no say: their
+  // rows are zero, every score is 0, and nobody reads their output.
+  if (__all(pad_query || (mx - st.top) * kC2 < -kSkip)) return;
+  // V^T operands: on their way while the exponentials are computed
+  bf16x8 va[4][4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) va[t][dt] = *(const bf16x8*)(vt + dt * (32 * 128) + t * 32);
   st.top = fmaxf(st.top, mx);
   if (__any((mx - st.m) * kC2 > kLazy)) {
     const float m_new = fmaxf(st.m, mx);
@@ -217,10 +230,7 @@ __device__ __forceinline__ void compute_tile(const unsigned char* const (&kaddr)
 #pragma unroll
   for (int t = 0; t < 4; ++t)
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) {
-      bf16x8 a = *(const bf16x8*)(vaddr[t] + dt * (32 * 128));
-      o[dt] = mfma(a, pf[t], o[dt]);
-    }
+    for (int dt = 0; dt < 4; ++dt) o[dt] = mfma(va[t][dt], pf[t], o[dt]);
 }
 
 __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const unsigned char* __restrict__ Qp,
@@ -257,22 +267,15 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   const int bw = (g + 31) >> 5;
   unsigned* ulist = bitmap + 4 * bw;                  // union entries: key block | (valid slots - 1) << 22 | membership << 28
   const int union_max = min(g, 4 * k);
-  int* ready = (int*)(smem + LDS_TOTAL - 64);         // [RING]
-  unsigned* passed = (unsigned*)(smem + LDS_TOTAL - 48);   // [RING]
-  int* next_load = (int*)(smem + LDS_TOTAL - 32);
-  int* freed = (int*)(smem + LDS_TOTAL - 28);
-  int* count = (int*)(smem + LDS_TOTAL - 24);
+  int* ctrl = (int*)(smem + LDS_TOTAL - 128);         // [32]: ready[8], prog[8], next_load, count, n_own
+  int* ready = ctrl;                                  // [RING]
+  int* prog = ctrl + 8;                               // [WAVES]
+  int* next_load = ctrl + 16;
+  int* count = ctrl + 17;                             // [2]
 
   // ---- union of the four lists
   for (int i = threadIdx.x; i < 4 * bw; i += 512) bitmap[i] = 0u;
-  if (threadIdx.x < RING) {
-    ready[threadIdx.x] = -1;
-    passed[threadIdx.x] = 0u;
-  }
-  if (threadIdx.x == 0) {
-    *next_load = 0;
-    *freed = 0;
-  }
+  if (threadIdx.x < 32) ctrl[threadIdx.x] = threadIdx.x < RING ? -1 : 0;
   __syncthreads();
   if (live && half == 0) {
     const int32_t* list = idx + qb * k;
@@ -336,7 +339,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
     unsigned* rest = ulist + n_own;                   // the own blocks keep their place in front
     const int nR = nU - n_own;
     unsigned* upos = ulist + union_max;               // position of an entry inside its class
-    int* ccount = (int*)(smem + LDS_TOTAL - 128);     // [16] entries per class
+    int* ccount = (int*)(smem + LDS_TOTAL - 256);     // [16] entries per class
     if (wave == 0) {
       int cc = 0;                                     // lane m keeps the running count of class m
       for (int base = 0; base < nR; base += 64) {
@@ -386,25 +389,19 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   const int r = lane & 31, hh = lane >> 5;
   const int krow = sigma(r);
   const int ke = (hh ^ (krow & 15)) << 4;
-  const int ve = (hh ^ ((r >> 1) & 7)) << 4;
-  int kofs[8], vofs[4];                               // operand offsets inside a slot, swizzle applied
+  int kofs[8];                                        // K operand offsets inside a slot, swizzle applied
 #pragma unroll
   for (int t = 0; t < 8; ++t) kofs[t] = krow * 256 + ((32 * t) ^ ke);
-#pragma unroll
-  for (int t = 0; t < 4; ++t) vofs[t] = K_TILE + r * 128 + ((32 * t) ^ ve);
   const unsigned ring_lds = (unsigned)(uintptr_t)(lds_bytes)smem;
-  unsigned koff[4], voff[4];
+  unsigned koff[4];
   tile_lane_offsets<256>(lane, koff);
-  tile_lane_offsets<128>(lane, voff);
   const unsigned char* Kbh = Kp + bh * q.n_pad * (D * 2);
-  const unsigned char* Vbh = Vt + bh * q.n_pad * (D * 2);
-  // one wave brings a whole tile (K and V^T of union entry u) into ring slot u % RING
+  const unsigned char* Vlane = Vt + bh * q.n_pad * (D * 2) + r * 128 + hh * 16;
+  // one wave brings the K tile of union entry u into ring slot u % RING
   auto issue_tile = [&](int u) {
     const unsigned e = ulist[u];
     const long long j = __builtin_amdgcn_readfirstlane((int)(e & 0x3fffffu));
-    const unsigned dst = ring_lds + (unsigned)(u & (RING - 1)) * SLOT;
-    dma_tile(Kbh + j * K_TILE, dst, koff);
-    dma_tile(Vbh + j * V_TILE, dst + K_TILE, voff);
+    dma_tile(Kbh + j * K_TILE, ring_lds + (unsigned)(u & (RING - 1)) * SLOT, koff);
   };
   int pending = -1;
   // a tile this wave has requested becomes visible to the others once it has landed
@@ -414,20 +411,6 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
       if (lane == 0) __atomic_store_n(&ready[pending & (RING - 1)], pending, __ATOMIC_RELAXED);
       pending = -1;
     }
-  };
-  auto try_request = [&]() -> bool {
-    const int L = __builtin_amdgcn_readfirstlane(__atomic_load_n(next_load, __ATOMIC_RELAXED));
-    if (L >= nU) return false;
-    const int fr = __builtin_amdgcn_readfirstlane(__atomic_load_n(freed, __ATOMIC_RELAXED));
-    if (L >= fr + RING) return false;
-    int got = L + 1;
-    if (lane == 0) got = atomicCAS(next_load, L, L + 1);
-    got = __builtin_amdgcn_readfirstlane(got);
-    if (got != L) return false;
-    publish();                                        // at most one request of mine is in flight
-    issue_tile(L);
-    pending = L;
-    return true;
   };
 
   // Q fragments: B operand, lane (query r, half-wave hh) holds d = 16t + 8hh .. +7
@@ -453,45 +436,80 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   for (int t = 0; t < 8; ++t) asm volatile("" : "+v"(qf[t]));
 
   const unsigned my_bit = live ? (1u << (28 + qblk)) : 0u;
+  const bool pad_query = 32 * half + r >= valid_slots(q, per_frame, pos);
+  // a look at the whole control block: lane i holds ctrl[i]
+  auto look = [&]() -> int { return __atomic_load_n(ctrl + (lane & 31), __ATOMIC_RELAXED); };
+  // request the next tile if the ring has room, judging by a look c (which may be old: then the
+  // compare-and-swap fails or the room is underestimated, both harmless)
+  auto service = [&](int c) {
+    if (pending >= 0) return;                         // at most one request of mine in flight
+    const int L = __builtin_amdgcn_readlane(c, 16);
+    if (L >= nU) return;
+    int fr = __builtin_amdgcn_readlane(c, 8);
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) fr = min(fr, __builtin_amdgcn_readlane(c, 8 + w));
+    if (L >= fr + RING) return;
+    int got = L + 1;
+    if (lane == 0) got = atomicCAS(next_load, L, L + 1);
+    got = __builtin_amdgcn_readfirstlane(got);
+    if (got != L) return;
+    issue_tile(L);
+    pending = L;
+  };
   bool gave_up = false;
-  for (int u = 0; u < nU && !gave_up; ++u) {
-    const int slot_i = u & (RING - 1);
+  int snap = look();
+  // The walk, 64 entries at a time: lane i holds entry base + i, a ballot tells which of them
+  // are mine.  Entries that are not mine cost nothing: prog jumps over them.
+  for (int base = 0; base < nU && !gave_up; base += 64) {
+    const unsigned e_lane = base + lane < nU ? ulist[base + lane] : 0u;
+    unsigned long long mine = __ballot((e_lane & my_bit) != 0u);
     {
-      try_request();
-      int spins = 0;
-      while (__builtin_amdgcn_readfirstlane(__atomic_load_n(&ready[slot_i], __ATOMIC_RELAXED)) != u) {
-        if (pending >= 0) {
-          publish();                                  // idle: wait for my own request and hand it over
-        } else if (!try_request()) {
-          __builtin_amdgcn_s_sleep(2);
-          if (++spins > kSpinLimit) {
-            gave_up = true;
-            break;
+      const int nxt = mine ? base + (int)__builtin_ctzll(mine) : min(base + 64, nU);
+      if (lane == 0) __atomic_store_n(&prog[wave], nxt, __ATOMIC_RELAXED);
+    }
+    while (mine) {
+      const int i = (int)__builtin_ctzll(mine);
+      mine &= mine - 1;
+      const int u = base + i;
+      const int slot_i = u & (RING - 1);
+      publish();                                      // my last request has had a whole tile's time to land
+      if (__builtin_amdgcn_readlane(snap, slot_i) != u) {
+        int spins = 0;
+        for (;;) {
+          snap = look();
+          service(snap);
+          if (__builtin_amdgcn_readlane(snap, slot_i) == u) break;
+          if (pending >= 0) {
+            publish();                                // idle anyway: wait for my own request and hand it over
+          } else {
+            __builtin_amdgcn_s_sleep(1);
+            if (++spins > kSpinLimit) {
+              gave_up = true;
+              break;
+            }
           }
         }
+        if (gave_up) break;
       }
-      if (gave_up) break;
-    }
-    const unsigned e = __builtin_amdgcn_readfirstlane(ulist[u]);
-    if (e & my_bit) {
-      const int nv = (int)((e >> 22) & 63u) + 1;
-      const unsigned char* slot = smem + slot_i * SLOT;
-      const unsigned char* kaddr[8];
-      const unsigned char* vaddr[4];
+      const int fresh = look();                       // asked for now, used after the tile: its latency hides behind the tile
+      const unsigned e = (unsigned)__builtin_amdgcn_readlane((int)e_lane, i);
+      {
+        const int nv = (int)((e >> 22) & 63u) + 1;
+        const unsigned char* slot = smem + slot_i * SLOT;
+        const unsigned char* kaddr[8];
 #pragma unroll
-      for (int t = 0; t < 8; ++t) kaddr[t] = slot + kofs[t];
-#pragma unroll
-      for (int t = 0; t < 4; ++t) vaddr[t] = slot + vofs[t];
-      compute_tile(kaddr, vaddr, hh, nv, qf, o, st);
-    }
-    {                                                 // my reads of the slot are complete: hand it back
+        for (int t = 0; t < 8; ++t) kaddr[t] = slot + kofs[t];
+        compute_tile(kaddr, Vlane + (long long)(e & 0x3fffffu) * V_TILE, hh, nv, pad_query, qf, o, st);
+      }
+      // my reads of the slot are complete: leave the entry, and those up to my next one, behind
       wait_lds();
-      if (lane == 0) {
-        unsigned old = atomicAdd(&passed[slot_i], 1u);
-        if (old + 1 == (unsigned)WAVES * (unsigned)((u >> 2) + 1)) __atomic_store_n(freed, u + 1, __ATOMIC_RELAXED);
+      {
+        const int nxt = mine ? base + (int)__builtin_ctzll(mine) : min(base + 64, nU);
+        if (lane == 0) __atomic_store_n(&prog[wave], nxt, __ATOMIC_RELAXED);
       }
+      snap = fresh;
+      service(snap);
     }
-    publish();
   }
   publish();
   __syncthreads();                                    // everyone is done with the ring: reuse it to stage the output
@@ -501,7 +519,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   unsigned char* stage = smem + wave * (RING_BYTES / WAVES);
   {
     const float lt = sum_across_halves(st.l);
-    const float inv = 1.0f / lt;
+    const float inv = lt > 0.f ? 1.0f / lt : 0.f;     // 0 only in pad query slots whose wave skipped every tile
     if (lse && hh == 0) lse[qb * BS + 32 * half + r] = st.m * kScale + __logf(lt);
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
@@ -534,7 +552,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
 int attn_bf16_ring_fits(const Geo& q) {
   if (q.g >= (1 << 22)) return 0;
   long long union_max = (long long)q.g < 4LL * q.k ? q.g : 4LL * q.k;
-  long long base = 4LL * 4 * ((q.g + 31) / 32) + 4 * union_max + 256;
+  long long base = 4LL * 4 * ((q.g + 31) / 32) + 4 * union_max + 512;
   if (base > ring::AUX_BYTES) return 0;
   return base + 8 * union_max <= ring::AUX_BYTES ? 2 : 1;
 }
