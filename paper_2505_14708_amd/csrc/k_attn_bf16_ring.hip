@@ -182,13 +182,19 @@ __device__ __forceinline__ void compute_tile(const unsigned char* const (&kaddr)
                                              int nv, bool pad_query, const bf16x8 (&qf)[8], f32x16 (&o)[4], Soft& st) {
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   f32x16 s0, s1;
-  // S^T = K Q^T
+  // S^T = K Q^T; all sixteen K operands are asked for before the first product, so the LDS
+  // latency is paid once per tile
+  bf16x8 ka[8], kb[8];
 #pragma unroll
   for (int t = 0; t < 8; ++t) {
-    bf16x8 a0 = *(const bf16x8*)(kaddr[t]);
-    bf16x8 a1 = *(const bf16x8*)(kaddr[t] + 32 * 256);
-    s0 = mfma(a0, qf[t], t == 0 ? zero : s0);
-    s1 = mfma(a1, qf[t], t == 0 ? zero : s1);
+    ka[t] = *(const bf16x8*)(kaddr[t]);
+    kb[t] = *(const bf16x8*)(kaddr[t] + 32 * 256);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    s0 = mfma(ka[t], qf[t], t == 0 ? zero : s0);
+    s1 = mfma(kb[t], qf[t], t == 0 ? zero : s1);
   }
   if (nv < BS) {
     mask_pad_half(s0, 0, nv, hh);
