@@ -40,9 +40,10 @@
 // not show up the wave gives up (its output is then wrong, but the kernel always ends).
 //
 // V does not go through LDS.  After S = QK^T of a tile a wave knows the largest score of each of
-// its queries; when every score of the tile is more than 30 powers of two below the best the
-// query has seen, the tile cannot change the result at the precision of the output and its
-// exponentials and second product are skipped.  With peaked attention that is the common case,
+// its queries; when every score of the tile is so far below the best the query has seen that
+// all such keys of a row together weigh less than 2^-14 of its largest term, the tile cannot
+// change the result at the precision of the output and its exponentials and second product are
+// skipped.  With peaked attention that is the common case,
 // so V^T operands are fetched from global memory (L2) straight into registers, only by the waves
 // that need them, while the exponentials are being computed.
 //
@@ -77,7 +78,7 @@ constexpr int O_STRIDE = D * 2 + 16;              // padded row stride of the ou
 constexpr float kScale = 0.08838834764831845f;                      // 1/sqrt(128)
 constexpr float kC2 = 0.08838834764831845f * 1.4426950408889634f;   // log2(e)/sqrt(128)
 constexpr float kLazy = 8.0f;                     // move the running max only past this many powers of two
-constexpr float kSkip = 30.0f;                    // tiles whose probabilities all stay below 2^-kSkip are dropped
+constexpr float kDropLog2 = 14.0f;                // all keys dropped from a row together weigh less than 2^-14 of its largest term
 constexpr int kSpinLimit = 1 << 20;
 
 // ---------------------------------------------------------------------------------- tile movement
@@ -179,7 +180,7 @@ struct Soft {
 // this lane's part of the tile's V^T in global memory: channel row r, 16-byte chunk hh; the
 // operand of (k-step t, channel group dt) is 32t bytes and 32dt rows further.
 __device__ __forceinline__ void compute_tile(const unsigned char* const (&kaddr)[8], const unsigned char* vt, int hh,
-                                             int nv, bool pad_query, const bf16x8 (&qf)[8], f32x16 (&o)[4], Soft& st) {
+                                             int nv, bool pad_query, float skip, const bf16x8 (&qf)[8], f32x16 (&o)[4], Soft& st) {
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   f32x16 s0, s1;
   // S^T = K Q^T; all sixteen K operands are asked for before the first product, so the LDS
@@ -202,13 +203,14 @@ __device__ __forceinline__ void compute_tile(const unsigned char* const (&kaddr)
   }
   // online softmax over the 64 keys
   const float mx = max_across_halves(max16(s1, max16(s0, -INFINITY)));   // finite: slot 0 of a block is valid
-  // A key whose score is more than kSkip powers of two below the query's best score so far
-  // weighs less than 2^-kSkip of that query's largest term, in the normaliser and in the output:
-  // far below the resolution of the result for any sequence length this kernel accepts.  When
-  // that holds for every key of the tile and all 32 queries, the exponentials and the second
+  // A key whose score is more than `skip` powers of two below the query's best score so far
+  // weighs less than 2^-skip of that query's largest term, in the normaliser and in the output.
+  // skip = log2(keys in the row) + kDropLog2, so whatever is dropped from a row adds up to less
+  // than 2^-kDropLog2 of that term: below the resolution of a bf16 result at any sequence length.
+  // When every key of the tile is that small for all 32 queries, the exponentials and the second
   // product are skipped.  (Never the first time: top is -inf.)  Pad query slots have no say: their
   // rows are zero, every score is 0, and nobody reads their output.
-  if (__all(pad_query || (mx - st.top) * kC2 < -kSkip)) return;
+  if (__all(pad_query || (mx - st.top) * kC2 < -skip)) return;
   // V^T operands: on their way while the exponentials are computed
   bf16x8 va[4][4];
 #pragma unroll
@@ -244,7 +246,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
                                                                const unsigned char* __restrict__ Vt,
                                                                const int32_t* __restrict__ idx,
                                                                unsigned char* __restrict__ Op, float* __restrict__ lse,
-                                                               int balance) {
+                                                               int balance, float skip) {
   __shared__ __attribute__((aligned(1024))) unsigned char smem[LDS_TOTAL];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
@@ -268,6 +270,16 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   const bool live = f < q.T;                          // a wave past the last frame only helps with the ring
   const long long qb = bh * q.g + (long long)min(f, q.T - 1) * per_frame + pos;
   const int k = q.k, g = q.g;
+
+  // Q fragments (B operand): lane (query r, half-wave hh) holds d = 16t + 8hh .. +7.  Asked for
+  // first, so that they arrive while the lists are being merged.
+  bf16x8 qf[8];
+  {
+    const int r = lane & 31, hh = lane >> 5;
+    const unsigned char* qbase = Qp + (qb * BS + 32 * half) * (D * 2);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) qf[t] = *(const bf16x8*)(qbase + r * (D * 2) + (16 * t + 8 * hh) * 2);
+  }
 
   unsigned* bitmap = (unsigned*)(smem + RING_BYTES);  // [4][bw] one bitmap of kept key blocks per query block
   const int bw = (g + 31) >> 5;
@@ -295,39 +307,49 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   // there, and the sooner the running maximum is near its final value, the more of the other
   // tiles turn out negligible.
   const int own_lo = (4 * (slot_id % fgs)) * per_frame + pos;   // own blocks: own_lo + w * per_frame, w = 0..3
-  if (wave == 0) {
+  // membership of key block j in the four lists (0 for the own blocks unless asked for)
+  auto membership = [&](int j, bool want_own) -> unsigned {
+    const int dj = j - own_lo;
+    const bool own = dj >= 0 && dj < 4 * per_frame && dj % per_frame == 0;
+    unsigned m4 = 0;
+    if (j < g && own == want_own) {
+#pragma unroll
+      for (int w = 0; w < 4; ++w) m4 |= ((bitmap[w * bw + (j >> 5)] >> (j & 31)) & 1u) << w;
+    }
+    return m4;
+  };
+  auto entry_of = [&](int j, unsigned m4) -> unsigned {
+    return (unsigned)j | ((unsigned)(valid_slots(q, per_frame, j) - 1) << 22) | (m4 << 28);
+  };
+  // every wave takes a contiguous eighth of the key blocks, 64 at a time: count, then place
+  int* wcount = ctrl + 20;                            // [WAVES]
+  const int chunks = (g + 63) >> 6, cpw = (chunks + WAVES - 1) / WAVES;
+  const int c_lo = wave * cpw, c_hi = min(chunks, c_lo + cpw);
+  {
     int cnt = 0;
-    {
-      const int j = own_lo + lane * per_frame;
-      unsigned m4 = 0;
-      if (lane < 4 && j < g) {
-#pragma unroll
-        for (int w = 0; w < 4; ++w) m4 |= ((bitmap[w * bw + (j >> 5)] >> (j & 31)) & 1u) << w;
-      }
-      unsigned long long nz = __ballot(m4 != 0);
-      int before = __builtin_amdgcn_mbcnt_hi((unsigned)(nz >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)nz, 0));
-      if (m4) ulist[before] = (unsigned)j | ((unsigned)(valid_slots(q, per_frame, j) - 1) << 22) | (m4 << 28);
-      cnt = __popcll(nz);
+    for (int c = c_lo; c < c_hi; ++c) cnt += __popcll(__ballot(membership(c * 64 + lane, false) != 0u));
+    if (lane == 0) wcount[wave] = cnt;
+    if (wave == 0) {
+      const unsigned m4 = lane < 4 ? membership(own_lo + lane * per_frame, true) : 0u;
+      const unsigned long long nz = __ballot(m4 != 0u);
+      const int before = __builtin_amdgcn_mbcnt_hi((unsigned)(nz >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)nz, 0));
+      if (m4) ulist[before] = entry_of(own_lo + lane * per_frame, m4);
+      if (lane == 0) count[1] = __popcll(nz);
     }
-    const int n_own = cnt;
-    for (int base = 0; base < g; base += 64) {
-      int j = base + lane;
-      unsigned m4 = 0;
-      const int dj = j - own_lo;
-      const bool own = dj >= 0 && dj < 4 * per_frame && dj % per_frame == 0;
-      if (j < g && !own) {
-#pragma unroll
-        for (int w = 0; w < 4; ++w) m4 |= ((bitmap[w * bw + (j >> 5)] >> (j & 31)) & 1u) << w;
-      }
-      unsigned long long nz = __ballot(m4 != 0);
-      int before = __builtin_amdgcn_mbcnt_hi((unsigned)(nz >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)nz, 0));
-      if (m4) ulist[cnt + before] = (unsigned)j | ((unsigned)(valid_slots(q, per_frame, j) - 1) << 22) | (m4 << 28);
-      cnt += __popcll(nz);
+  }
+  __syncthreads();
+  {
+    int at = count[1];
+    for (int w = 0; w < wave; ++w) at += wcount[w];
+    for (int c = c_lo; c < c_hi; ++c) {
+      const int j = c * 64 + lane;
+      const unsigned m4 = membership(j, false);
+      const unsigned long long nz = __ballot(m4 != 0u);
+      const int before = __builtin_amdgcn_mbcnt_hi((unsigned)(nz >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)nz, 0));
+      if (m4) ulist[at + before] = entry_of(j, m4);
+      at += __popcll(nz);
     }
-    if (lane == 0) {
-      count[0] = cnt;
-      count[1] = n_own;
-    }
+    if (wave == WAVES - 1 && lane == 0) count[0] = at;
   }
   __syncthreads();
   const int nU = __builtin_amdgcn_readfirstlane(count[0]);
@@ -371,17 +393,26 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
       const int m = (int)(e >> 28);
       const int c = ccount[m];
       const int a2 = 2 * (int)upos[i] + 1;            // my key is a2 / (2c)
+      const float rc = 1.0f / (float)c;
       int rank = 0;
 #pragma unroll
       for (int m2 = 1; m2 < 16; ++m2) {
         const int c2 = ccount[m2];
         if (c2 == 0) continue;
         // entries j of class m2 with (2j+1)/(2 c2) < a2/(2c), i.e. (2j+1) c < a2 c2
-        const int A = a2 * c2;
-        const int qq = (A + c - 1) / c;               // ceil(A / c)
-        int cntl = qq >> 1;
+        const int A = a2 * c2;                        // below 2^24 (the lists fit in LDS): exact in float
+        int fl = (int)((float)A * rc);                // floor(A / c) up to one unit, put right below
+        int rem = A - fl * c;
+        if (rem < 0) {
+          fl -= 1;
+          rem += c;
+        } else if (rem >= c) {
+          fl += 1;
+          rem -= c;
+        }
+        int cntl = (fl + (rem != 0)) >> 1;            // ceil(A / c) / 2
         // an exact tie goes to the lower class number
-        if (m2 < m && A % c == 0 && ((A / c) & 1)) cntl += 1;
+        if (m2 < m && rem == 0 && (fl & 1)) cntl += 1;
         rank += min(cntl, c2);
       }
       sorted[rank] = e;
@@ -419,13 +450,6 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
     }
   };
 
-  // Q fragments: B operand, lane (query r, half-wave hh) holds d = 16t + 8hh .. +7
-  bf16x8 qf[8];
-  {
-    const unsigned char* qbase = Qp + (qb * BS + 32 * half) * (D * 2);
-#pragma unroll
-    for (int t = 0; t < 8; ++t) qf[t] = *(const bf16x8*)(qbase + r * (D * 2) + (16 * t + 8 * hh) * 2);
-  }
   f32x16 o[4];
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
@@ -505,7 +529,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
         const unsigned char* kaddr[8];
 #pragma unroll
         for (int t = 0; t < 8; ++t) kaddr[t] = slot + kofs[t];
-        compute_tile(kaddr, Vlane + (long long)(e & 0x3fffffu) * V_TILE, hh, nv, pad_query, qf, o, st);
+        compute_tile(kaddr, Vlane + (long long)(e & 0x3fffffu) * V_TILE, hh, nv, pad_query, skip, qf, o, st);
       }
       // my reads of the slot are complete: leave the entry, and those up to my next one, behind
       wait_lds();
@@ -569,7 +593,7 @@ hipError_t launch_attn_bf16_ring(const Geo& q, const void* Qp, const void* Kp, c
   unsigned grid = (unsigned)((long long)q.B * q.H * 8 * ((per_frame + 7) / 8) * ((q.T + 3) / 4));
   hipLaunchKernelGGL(ring::attn_bf16_ring_kernel, dim3(grid), dim3(512), 0, s, q, (const unsigned char*)Qp,
                      (const unsigned char*)Kp, (const unsigned char*)Vt, idx, (unsigned char*)Op, lse,
-                     attn_bf16_ring_fits(q) == 2 ? 1 : 0);
+                     attn_bf16_ring_fits(q) == 2 ? 1 : 0, log2f((float)q.k * (float)ring::BS) + ring::kDropLog2);
   return hipGetLastError();
 }
 
