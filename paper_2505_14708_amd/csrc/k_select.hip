@@ -1,11 +1,13 @@
 // Guided sparsity: per row of the draft scores keep the k largest entries (ties to the
 // lowest column) and emit their columns in ascending order.
 //
-// One wavefront per row.  The row is mapped to order-preserving 32-bit keys held in LDS; the
-// value of the k-th largest key is found bit by bit from the top (32 counting passes over
-// LDS, each a wave-wide popcount reduction); one more ordered pass writes every column
-// whose key beats the threshold plus the first (k - #greater) columns that equal it, using
-// ballot + lane-prefix popcounts so the output stays in column order without any sort.
+// One wavefront per row.  The row is mapped to order-preserving 32-bit keys; the value of the
+// k-th largest key is found bit by bit from the top (32 counting passes); one more ordered pass
+// writes every column whose key beats the threshold plus the first (k - #greater) columns that
+// equal it, using ballot + lane-prefix popcounts so the output stays in column order without
+// any sort.  Rows of up to 4096 columns are held in registers (lane l keeps columns l, l + 64,
+// ...): a counting pass is then one compare per key, whose lane mask is counted on the scalar
+// unit.  Longer rows keep their keys in LDS, or recompute them from global memory.
 #include "da_internal.h"
 
 namespace da {
@@ -72,10 +74,62 @@ __global__ __launch_bounds__(64) void select_kernel(const float* __restrict__ sc
   }
 }
 
+
+// Keys in registers: KPL keys per lane, column of key i of lane l is l + 64 i.
+template <int KPL>
+__global__ __launch_bounds__(64) void select_reg_kernel(const float* __restrict__ scores, int32_t* __restrict__ idx,
+                                                        uint8_t* __restrict__ mask, int g, int k) {
+  const long long row = blockIdx.x;
+  const int lane = threadIdx.x;
+  const float* in = scores + row * g;
+  unsigned key[KPL];
+#pragma unroll
+  for (int i = 0; i < KPL; ++i) {
+    const int j = lane + 64 * i;
+    key[i] = j < g ? order_key(in[j]) : 0u;           // a column past the end never counts: every trial value is > 0
+  }
+  unsigned thr = 0u;
+  for (int bit = 31; bit >= 0; --bit) {
+    const unsigned cand = thr | (1u << bit);
+    int cnt = 0;
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) cnt += __popcll(__ballot(key[i] >= cand));
+    if (cnt >= k) thr = cand;
+  }
+  // thr is now the k-th largest key
+  int gt = 0;
+#pragma unroll
+  for (int i = 0; i < KPL; ++i) gt += __popcll(__ballot(key[i] > thr));
+  const int need_eq = k - gt;
+  int written = 0, eq_seen = 0;
+  int32_t* out = idx + row * k;
+  uint8_t* mrow = mask ? mask + row * g : nullptr;
+#pragma unroll
+  for (int i = 0; i < KPL; ++i) {
+    const int j = lane + 64 * i;
+    if (64 * i >= g) break;                           // uniform
+    const bool is_gt = j < g && key[i] > thr;
+    const bool is_eq = j < g && key[i] == thr;
+    const unsigned long long eq_mask = __ballot(is_eq);
+    const bool take = is_gt || (is_eq && eq_seen + lane_prefix(eq_mask) < need_eq);
+    const unsigned long long take_mask = __ballot(take);
+    if (take) out[written + lane_prefix(take_mask)] = j;
+    if (mrow && j < g) mrow[j] = take ? 1 : 0;
+    written += __popcll(take_mask);
+    eq_seen += __popcll(eq_mask);
+  }
+}
+
 hipError_t launch_select(const Geo& q, const float* scores, int32_t* idx, uint8_t* mask, hipStream_t s) {
   long long rows = (long long)q.B * q.H * q.g;
   size_t lds = (size_t)q.g * sizeof(unsigned);
-  if (lds <= 64 * 1024)
+  if (q.g <= 64 * 16)
+    hipLaunchKernelGGL(select_reg_kernel<16>, dim3((unsigned)rows), dim3(64), 0, s, scores, idx, mask, q.g, q.k);
+  else if (q.g <= 64 * 32)
+    hipLaunchKernelGGL(select_reg_kernel<32>, dim3((unsigned)rows), dim3(64), 0, s, scores, idx, mask, q.g, q.k);
+  else if (q.g <= 64 * 64)
+    hipLaunchKernelGGL(select_reg_kernel<64>, dim3((unsigned)rows), dim3(64), 0, s, scores, idx, mask, q.g, q.k);
+  else if (lds <= 64 * 1024)
     hipLaunchKernelGGL(select_kernel<true>, dim3((unsigned)rows), dim3(64), lds, s, scores, idx, mask, q.g, q.k);
   else
     hipLaunchKernelGGL(select_kernel<false>, dim3((unsigned)rows), dim3(64), 0, s, scores, idx, mask, q.g, q.k);

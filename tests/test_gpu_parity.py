@@ -206,6 +206,29 @@ def test_select_planted_rows(torch_mod):
         assert np.array_equal(mask.cpu().numpy(), rmask), (g, k)
 
 
+def test_select_long_rows(torch_mod):
+    """Rows too long for the register-resident selector: keys in LDS (g = 4500) and keys recomputed
+    from global memory (g = 16400).  The oracle ranks the planted rows and a sample of the others."""
+    torch = torch_mod
+    rng = np.random.default_rng(8)
+    for (g, k) in [(4500, 450), (16400, 300)]:
+        say(f"select long rows g={g}")
+        L = rng.standard_normal(size=(g, g), dtype=np.float32)
+        L[0, :] = 0.0
+        L[1, :] = np.round(L[1] * 2) / 2
+        L[2, ::2] = 0.0; L[2, 1::2] = -0.0
+        L[3, :] = -np.arange(g, dtype=np.float32)
+        L[4, :] = np.arange(g, dtype=np.float32)
+        p = da.problem(1, 1, g, 8, 8, 128, keep_blocks=k)
+        assert da.da_derive(p).g == g and da.da_derive(p).k == k
+        idx = torch.empty((g, k), dtype=torch.int32, device="cuda")
+        da.da_select_blocks(p, torch.from_numpy(L).cuda(), idx, None)
+        torch.cuda.synchronize()
+        rows = np.unique(np.concatenate([np.arange(8), rng.integers(0, g, 64), [g - 1]]))
+        ridx, _ = oa.select_blocks(L[rows], k)
+        assert np.array_equal(idx.cpu().numpy()[rows], ridx), (g, k)
+
+
 # ----------------------------------------------------------------------------- SparseAttn
 def _attn_inputs(torch, w, Q, K, V, refs, idx_np):
     p = da.problem_of(w)
