@@ -197,12 +197,11 @@ int da_forward(const da_problem* p, const void* Q, const void* K, const void* V,
   hipError_t e;
   // Definition 3.2: pooled Q~, K~ and the draft logits (the ranking of a row of the draft
   // map is the ranking of its logits, so the softmax itself is not needed here)
-  if ((e = launch_pool(q, Q, K, q_pool, k_pool, s)) != hipSuccess) return DA_ERR_HIP;
+  // (the pooling pass also writes the reordered Q and K of Algorithm 1: one read of Q and K for both)
+  if ((e = launch_pool_reorder(q, Q, K, q_pool, k_pool, qp, kp, s)) != hipSuccess) return DA_ERR_HIP;
   if ((e = launch_draft_logits(q, q_pool, k_pool, logits, s)) != hipSuccess) return DA_ERR_HIP;
   if ((e = launch_select(q, logits, idx, nullptr, s)) != hipSuccess) return DA_ERR_HIP;
-  // Algorithm 1: reorder
-  if ((e = launch_permute(q, Q, qp, DA_REORDER_ROWS, s)) != hipSuccess) return DA_ERR_HIP;
-  if ((e = launch_permute(q, K, kp, DA_REORDER_ROWS, s)) != hipSuccess) return DA_ERR_HIP;
+  // Algorithm 1: reorder V (block-transposed)
   if ((e = launch_permute(q, V, vt, DA_REORDER_VT, s)) != hipSuccess) return DA_ERR_HIP;
   // SparseAttn
   if (q.dtype == DA_BF16)

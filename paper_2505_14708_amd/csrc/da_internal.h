@@ -57,6 +57,9 @@ __host__ __device__ inline long long token_slot(const Geo& q, long long n) {
 hipError_t launch_build_perm(const Geo& q, int32_t* perm, int32_t* inv, int32_t* valid, hipStream_t s);
 hipError_t launch_permute(const Geo& q, const void* X, void* Y, int mode, hipStream_t s);
 hipError_t launch_pool(const Geo& q, const void* Q, const void* K, float* q_pool, float* k_pool, hipStream_t s);
+// pooling and the reordering of Q and K (DA_REORDER_ROWS layout) in one pass over Q and K
+hipError_t launch_pool_reorder(const Geo& q, const void* Q, const void* K, float* q_pool, float* k_pool, void* Qp,
+                               void* Kp, hipStream_t s);
 hipError_t launch_draft_logits(const Geo& q, const float* q_pool, const float* k_pool, float* logits, hipStream_t s);
 hipError_t launch_row_softmax(const Geo& q, const float* logits, float* draft, hipStream_t s);
 hipError_t launch_select(const Geo& q, const float* scores, int32_t* idx, uint8_t* mask, hipStream_t s);

@@ -32,10 +32,13 @@ struct Vec<DA_F32> {
   }
 };
 
-// grid.x covers (bh, block, chunk) items; grid.y = 0 for Q, 1 for K.
-template <int DT>
+// grid.x covers (bh, block, chunk) items; grid.y = 0 for Q, 1 for K.  With REORDER the tokens are
+// also written, as they go by, to their slots of the reordered tensors Qp, Kp (Algorithm 1), pad
+// slots zeroed: pooling and reordering then read Q and K once between them.
+template <int DT, bool REORDER>
 __global__ __launch_bounds__(256) void pool_kernel(Geo q, const uint4* __restrict__ Q, const uint4* __restrict__ K,
-                                                   float* __restrict__ q_pool, float* __restrict__ k_pool, int cpr,
+                                                   float* __restrict__ q_pool, float* __restrict__ k_pool,
+                                                   uint4* __restrict__ Qp, uint4* __restrict__ Kp, int cpr,
                                                    long long items) {
   constexpr int N = Vec<DT>::N;
   long long item = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -48,6 +51,7 @@ __global__ __launch_bounds__(256) void pool_kernel(Geo q, const uint4* __restric
   int i = (int)(blk - bh * q.g);
   BlockPos b = block_pos(q, i);
   const uint4* src = X + (bh * q.n + ((long long)b.f * q.fh + b.y0) * q.fw + b.x0) * cpr + c;
+  uint4* dstp = REORDER ? (blockIdx.y ? Kp : Qp) + (blk * q.block) * cpr + c : nullptr;   // slot 0 of the block
   float acc[N];
 #pragma unroll
   for (int j = 0; j < N; ++j) acc[j] = 0.f;
@@ -60,6 +64,7 @@ __global__ __launch_bounds__(256) void pool_kernel(Geo q, const uint4* __restric
       for (int t = 0; t < 8; ++t) r[t] = row[(long long)(v + t) * cpr];
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
+        if (REORDER) dstp[(long long)(u * b.vw + v + t) * cpr] = r[t];
         float f[N];
         Vec<DT>::widen(r[t], f);
 #pragma unroll
@@ -67,12 +72,16 @@ __global__ __launch_bounds__(256) void pool_kernel(Geo q, const uint4* __restric
       }
     }
     for (; v < b.vw; ++v) {
+      const uint4 rv = row[(long long)v * cpr];
+      if (REORDER) dstp[(long long)(u * b.vw + v) * cpr] = rv;
       float f[N];
-      Vec<DT>::widen(row[(long long)v * cpr], f);
+      Vec<DT>::widen(rv, f);
 #pragma unroll
       for (int j = 0; j < N; ++j) acc[j] = acc[j] + f[j];
     }
   }
+  if (REORDER)
+    for (int sl = b.vh * b.vw; sl < q.block; ++sl) dstp[(long long)sl * cpr] = make_uint4(0u, 0u, 0u, 0u);
   float cnt = (float)(b.vh * b.vw);
   float* dst = out + blk * q.d + c * N;
 #pragma unroll
@@ -80,16 +89,26 @@ __global__ __launch_bounds__(256) void pool_kernel(Geo q, const uint4* __restric
 }
 
 hipError_t launch_pool(const Geo& q, const void* Q, const void* K, float* q_pool, float* k_pool, hipStream_t s) {
+  return launch_pool_reorder(q, Q, K, q_pool, k_pool, nullptr, nullptr, s);
+}
+
+// Qp, Kp both NULL: pooling only
+hipError_t launch_pool_reorder(const Geo& q, const void* Q, const void* K, float* q_pool, float* k_pool, void* Qp,
+                               void* Kp, hipStream_t s) {
   size_t es = q.dtype == DA_BF16 ? 2 : 4;
   int cpr = (int)(q.d * es / 16);
   long long items = (long long)q.B * q.H * q.g * cpr;
   dim3 grid((unsigned)((items + 255) / 256), 2);
-  if (q.dtype == DA_BF16)
-    hipLaunchKernelGGL(pool_kernel<DA_BF16>, grid, dim3(256), 0, s, q, (const uint4*)Q, (const uint4*)K, q_pool, k_pool,
-                       cpr, items);
-  else
-    hipLaunchKernelGGL(pool_kernel<DA_F32>, grid, dim3(256), 0, s, q, (const uint4*)Q, (const uint4*)K, q_pool, k_pool,
-                       cpr, items);
+  const bool re = Qp != nullptr;
+#define DA_POOL_LAUNCH(DT, RE)                                                                                        \
+  hipLaunchKernelGGL((pool_kernel<DT, RE>), grid, dim3(256), 0, s, q, (const uint4*)Q, (const uint4*)K, q_pool, k_pool, \
+                     (uint4*)Qp, (uint4*)Kp, cpr, items)
+  if (q.dtype == DA_BF16) {
+    if (re) DA_POOL_LAUNCH(DA_BF16, true); else DA_POOL_LAUNCH(DA_BF16, false);
+  } else {
+    if (re) DA_POOL_LAUNCH(DA_F32, true); else DA_POOL_LAUNCH(DA_F32, false);
+  }
+#undef DA_POOL_LAUNCH
   return hipGetLastError();
 }
 
