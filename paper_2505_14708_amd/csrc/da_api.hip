@@ -68,11 +68,13 @@ Workspace plan_workspace(const Geo& q) {
   size_t bh = (size_t)q.B * q.H;
   size_t big = align_up(bh * (size_t)q.n_pad * q.d * elem_size(q));
   size_t pooled = align_up(bh * (size_t)q.g * q.d * sizeof(float));
+  // the bf16 attention kernel reads Q and writes O in the original token order: no reordered copies of them
+  const bool direct = q.dtype == DA_BF16;
   size_t off = 0;
-  w.qp = off; off += big;
+  w.qp = off; off += direct ? 0 : big;
   w.kp = off; off += big;
   w.vt = off; off += big;
-  w.op = off; off += big;
+  w.op = off; off += direct ? 0 : big;
   w.q_pool = off; off += pooled;
   w.k_pool = off; off += pooled;
   w.logits = off; off += align_up(bh * (size_t)q.g * q.g * sizeof(float));
@@ -168,7 +170,7 @@ int da_sparse_attn(const da_problem* p, const void* Qp, const void* Kp, const vo
     return DA_ERR_ALIGN;
   if (!attn_supported(q)) return DA_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
-  if (q.dtype == DA_BF16) return hip_status(launch_attn_bf16_ring(q, Qp, Kp, Vt, idx, Op, lse, s));
+  if (q.dtype == DA_BF16) return hip_status(launch_attn_bf16_ring(q, Qp, Kp, Vt, idx, Op, lse, false, s));
   return hip_status(launch_attn_f32(q, (const float*)Qp, (const float*)Kp, (const float*)Vt, idx, (float*)Op, lse, s));
 }
 
@@ -197,17 +199,24 @@ int da_forward(const da_problem* p, const void* Q, const void* K, const void* V,
   hipError_t e;
   // Definition 3.2: pooled Q~, K~ and the draft logits (the ranking of a row of the draft
   // map is the ranking of its logits, so the softmax itself is not needed here)
-  // (the pooling pass also writes the reordered Q and K of Algorithm 1: one read of Q and K for both)
+  if (q.dtype == DA_BF16) {
+    // The pooling pass also writes the reordered K of Algorithm 1 (one read of K for both).  Q is
+    // not copied at all: the attention kernel reads its query rows from their original places and
+    // writes O's rows back to theirs, which is Algorithm 1 for Q and Algorithm 2 for O done by
+    // addressing (a row of 256 bytes is contiguous in either order).
+    if ((e = launch_pool_reorder(q, Q, K, q_pool, k_pool, nullptr, kp, s)) != hipSuccess) return DA_ERR_HIP;
+    if ((e = launch_draft_logits(q, q_pool, k_pool, logits, s)) != hipSuccess) return DA_ERR_HIP;
+    if ((e = launch_select(q, logits, idx, nullptr, s)) != hipSuccess) return DA_ERR_HIP;
+    if ((e = launch_permute(q, V, vt, DA_REORDER_VT, s)) != hipSuccess) return DA_ERR_HIP;
+    return hip_status(launch_attn_bf16_ring(q, Q, kp, vt, idx, O, nullptr, true, s));
+  }
   if ((e = launch_pool_reorder(q, Q, K, q_pool, k_pool, qp, kp, s)) != hipSuccess) return DA_ERR_HIP;
   if ((e = launch_draft_logits(q, q_pool, k_pool, logits, s)) != hipSuccess) return DA_ERR_HIP;
   if ((e = launch_select(q, logits, idx, nullptr, s)) != hipSuccess) return DA_ERR_HIP;
   // Algorithm 1: reorder V (block-transposed)
   if ((e = launch_permute(q, V, vt, DA_REORDER_VT, s)) != hipSuccess) return DA_ERR_HIP;
   // SparseAttn
-  if (q.dtype == DA_BF16)
-    e = launch_attn_bf16_ring(q, qp, kp, vt, idx, op, nullptr, s);
-  else
-    e = launch_attn_f32(q, (const float*)qp, (const float*)kp, (const float*)vt, idx, (float*)op, nullptr, s);
+  e = launch_attn_f32(q, (const float*)qp, (const float*)kp, (const float*)vt, idx, (float*)op, nullptr, s);
   if (e != hipSuccess) return DA_ERR_HIP;
   // Algorithm 2: restore
   return hip_status(launch_permute(q, op, O, DA_RESTORE, s));

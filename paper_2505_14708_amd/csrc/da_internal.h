@@ -67,7 +67,8 @@ hipError_t launch_attn_f32(const Geo& q, const float* Qp, const float* Kp, const
                            float* Op, float* lse, hipStream_t s);
 // bf16 block-sparse attention (k_attn_bf16_ring.hip)
 int attn_bf16_ring_fits(const Geo& q);
+// direct: Qp and Op are Q and O in the original token order (lse stays in slot order)
 hipError_t launch_attn_bf16_ring(const Geo& q, const void* Qp, const void* Kp, const void* Vt, const int32_t* idx,
-                                 void* Op, float* lse, hipStream_t s);
+                                 void* Op, float* lse, bool direct, hipStream_t s);
 
 }  // namespace da

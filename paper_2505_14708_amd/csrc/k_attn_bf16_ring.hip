@@ -246,7 +246,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
                                                                const unsigned char* __restrict__ Vt,
                                                                const int32_t* __restrict__ idx,
                                                                unsigned char* __restrict__ Op, float* __restrict__ lse,
-                                                               int balance, float skip) {
+                                                               int balance, float skip, int direct) {
   __shared__ __attribute__((aligned(1024))) unsigned char smem[LDS_TOTAL];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
@@ -273,12 +273,29 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
 
   // Q fragments (B operand): lane (query r, half-wave hh) holds d = 16t + 8hh .. +7.  Asked for
   // first, so that they arrive while the lists are being merged.
+  // With `direct`, Qp and Op are Q and O in the original token order: the reordering of Q and the
+  // restoring of O (Algorithms 1 and 2) are then this kernel's addressing, slot -> token.
+  const BlockPos qpos = block_pos(q, (int)(min(f, q.T - 1) * per_frame + pos));
+  // row of slot s of my query block in Qp / Op, or -1 (pad slot of the original order)
+  auto row_of = [&](int s) -> long long {
+    if (!direct) return qb * BS + s;
+    if (s >= qpos.vh * qpos.vw) return -1;
+    const int u = s / qpos.vw, v = s - u * qpos.vw;
+    return bh * q.n + ((long long)qpos.f * q.fh + qpos.y0 + u) * q.fw + qpos.x0 + v;
+  };
   bf16x8 qf[8];
   {
     const int r = lane & 31, hh = lane >> 5;
-    const unsigned char* qbase = Qp + (qb * BS + 32 * half) * (D * 2);
+    const long long row = row_of(32 * half + r);
+    const unsigned char* qrow = Qp + max(row, 0LL) * (D * 2);
 #pragma unroll
-    for (int t = 0; t < 8; ++t) qf[t] = *(const bf16x8*)(qbase + r * (D * 2) + (16 * t + 8 * hh) * 2);
+    for (int t = 0; t < 8; ++t) {
+      qf[t] = *(const bf16x8*)(qrow + (16 * t + 8 * hh) * 2);
+      if (row < 0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) qf[t][i] = (__bf16)0.f;
+      }
+    }
   }
 
   unsigned* bitmap = (unsigned*)(smem + RING_BYTES);  // [4][bw] one bitmap of kept key blocks per query block
@@ -566,11 +583,11 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   }
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
   __builtin_amdgcn_wave_barrier();
-  unsigned char* obase = Op + (qb * BS + 32 * half) * (D * 2);
 #pragma unroll
   for (int it = 0; it < 8; ++it) {
-    int row = it * 4 + (lane >> 4), ch = lane & 15;
-    *(uint4*)(obase + row * (D * 2) + ch * 16) = *(const uint4*)(stage + row * O_STRIDE + ch * 16);
+    const int row = it * 4 + (lane >> 4), ch = lane & 15;
+    const long long orow = row_of(32 * half + row);
+    if (orow >= 0) *(uint4*)(Op + orow * (D * 2) + ch * 16) = *(const uint4*)(stage + row * O_STRIDE + ch * 16);
   }
 }
 
@@ -588,12 +605,12 @@ int attn_bf16_ring_fits(const Geo& q) {
 }
 
 hipError_t launch_attn_bf16_ring(const Geo& q, const void* Qp, const void* Kp, const void* Vt, const int32_t* idx,
-                                 void* Op, float* lse, hipStream_t s) {
+                                 void* Op, float* lse, bool direct, hipStream_t s) {
   const int per_frame = q.gh * q.gw;
   unsigned grid = (unsigned)((long long)q.B * q.H * 8 * ((per_frame + 7) / 8) * ((q.T + 3) / 4));
   hipLaunchKernelGGL(ring::attn_bf16_ring_kernel, dim3(grid), dim3(512), 0, s, q, (const unsigned char*)Qp,
                      (const unsigned char*)Kp, (const unsigned char*)Vt, idx, (unsigned char*)Op, lse,
-                     attn_bf16_ring_fits(q) == 2 ? 1 : 0, log2f((float)q.k * (float)ring::BS) + ring::kDropLog2);
+                     attn_bf16_ring_fits(q) == 2 ? 1 : 0, log2f((float)q.k * (float)ring::BS) + ring::kDropLog2, direct ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -51,7 +51,9 @@ __global__ __launch_bounds__(256) void pool_kernel(Geo q, const uint4* __restric
   int i = (int)(blk - bh * q.g);
   BlockPos b = block_pos(q, i);
   const uint4* src = X + (bh * q.n + ((long long)b.f * q.fh + b.y0) * q.fw + b.x0) * cpr + c;
-  uint4* dstp = REORDER ? (blockIdx.y ? Kp : Qp) + (blk * q.block) * cpr + c : nullptr;   // slot 0 of the block
+  uint4* const dbase = blockIdx.y ? Kp : Qp;          // NULL: this tensor is only pooled
+  const bool wr = REORDER && dbase != nullptr;
+  uint4* dstp = wr ? dbase + (blk * q.block) * cpr + c : nullptr;   // slot 0 of the block
   float acc[N];
 #pragma unroll
   for (int j = 0; j < N; ++j) acc[j] = 0.f;
@@ -64,7 +66,7 @@ __global__ __launch_bounds__(256) void pool_kernel(Geo q, const uint4* __restric
       for (int t = 0; t < 8; ++t) r[t] = row[(long long)(v + t) * cpr];
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
-        if (REORDER) dstp[(long long)(u * b.vw + v + t) * cpr] = r[t];
+        if (wr) dstp[(long long)(u * b.vw + v + t) * cpr] = r[t];
         float f[N];
         Vec<DT>::widen(r[t], f);
 #pragma unroll
@@ -73,14 +75,14 @@ __global__ __launch_bounds__(256) void pool_kernel(Geo q, const uint4* __restric
     }
     for (; v < b.vw; ++v) {
       const uint4 rv = row[(long long)v * cpr];
-      if (REORDER) dstp[(long long)(u * b.vw + v) * cpr] = rv;
+      if (wr) dstp[(long long)(u * b.vw + v) * cpr] = rv;
       float f[N];
       Vec<DT>::widen(rv, f);
 #pragma unroll
       for (int j = 0; j < N; ++j) acc[j] = acc[j] + f[j];
     }
   }
-  if (REORDER)
+  if (wr)
     for (int sl = b.vh * b.vw; sl < q.block; ++sl) dstp[(long long)sl * cpr] = make_uint4(0u, 0u, 0u, 0u);
   float cnt = (float)(b.vh * b.vw);
   float* dst = out + blk * q.d + c * N;
@@ -92,14 +94,14 @@ hipError_t launch_pool(const Geo& q, const void* Q, const void* K, float* q_pool
   return launch_pool_reorder(q, Q, K, q_pool, k_pool, nullptr, nullptr, s);
 }
 
-// Qp, Kp both NULL: pooling only
+// Qp, Kp: each may be NULL (that tensor is then only pooled)
 hipError_t launch_pool_reorder(const Geo& q, const void* Q, const void* K, float* q_pool, float* k_pool, void* Qp,
                                void* Kp, hipStream_t s) {
   size_t es = q.dtype == DA_BF16 ? 2 : 4;
   int cpr = (int)(q.d * es / 16);
   long long items = (long long)q.B * q.H * q.g * cpr;
   dim3 grid((unsigned)((items + 255) / 256), 2);
-  const bool re = Qp != nullptr;
+  const bool re = Qp != nullptr || Kp != nullptr;
 #define DA_POOL_LAUNCH(DT, RE)                                                                                        \
   hipLaunchKernelGGL((pool_kernel<DT, RE>), grid, dim3(256), 0, s, q, (const uint4*)Q, (const uint4*)K, q_pool, k_pool, \
                      (uint4*)Qp, (uint4*)Kp, cpr, items)
