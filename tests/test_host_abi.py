@@ -100,7 +100,7 @@ def test_forward_workspace_checks():
     assert L.da_forward(*args[:-1], None, ctypes.c_size_t(need), None) == -1
     # the workspace of the headline configuration is a few GB, far below one GPU's HBM
     big = da.da_workspace_size(da.problem_of(W.CONFIGS["720p_hunyuan"]))
-    assert 3.0e9 < big < 6.0e9
+    assert 1.5e9 < big < 6.0e9
 
 
 def test_status_strings():
