@@ -460,9 +460,10 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   int pending = -1;
   // a tile this wave has requested becomes visible to the others once it has landed
   auto publish = [&]() {
-    if (pending >= 0) {
+    const int pd = __builtin_amdgcn_readfirstlane(pending);   // (the same in every lane; says so to the compiler)
+    if (pd >= 0) {
       wait_vm0();
-      if (lane == 0) __atomic_store_n(&ready[pending & (RING - 1)], pending, __ATOMIC_RELAXED);
+      if (lane == 0) __atomic_store_n(&ready[pd & (RING - 1)], pd, __ATOMIC_RELAXED);
       pending = -1;
     }
   };
@@ -489,7 +490,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   // request the next tile if the ring has room, judging by a look c (which may be old: then the
   // compare-and-swap fails or the room is underestimated, both harmless)
   auto service = [&](int c) {
-    if (pending >= 0) return;                         // at most one request of mine in flight
+    if (__builtin_amdgcn_readfirstlane(pending) >= 0) return;   // at most one request of mine in flight
     const int L = __builtin_amdgcn_readlane(c, 16);
     if (L >= nU) return;
     int fr = __builtin_amdgcn_readlane(c, 8);
@@ -526,7 +527,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
           snap = look();
           service(snap);
           if (__builtin_amdgcn_readlane(snap, slot_i) == u) break;
-          if (pending >= 0) {
+          if (__builtin_amdgcn_readfirstlane(pending) >= 0) {
             publish();                                // idle anyway: wait for my own request and hand it over
           } else {
             __builtin_amdgcn_s_sleep(1);
