@@ -10,7 +10,9 @@ heads of 128, 8x8 pooling, 90 % sparsity, bf16.  Prints ONE JSON line.
   ms_per_step  milliseconds per layer (the other half of the metric)
   roofline     the block-sparse attention kernel against the bf16 MFMA peak; its launch
                duration is measured with HIP events on the launch stream in a second loop
-               that issues the same kernels stage by stage through the C ABI
+               that issues the C-ABI stages one by one (da_forward fuses some of them: it
+               reorders K inside the pooling pass and makes no reordered copies of Q and O,
+               so ms_per_step is smaller than the sum of stages_ms)
   cpu_baseline the NumPy float64 oracle timed on this host on a bounded sample
 """
 from __future__ import annotations
@@ -35,7 +37,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 # HBM-side bytes per launch of the attention kernel (read, written), from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this program, scaled by what the same counters read for the row-copy kernel of known
 # size in the same run (profiles/pmc_traffic_720p_hunyuan.txt).  Workloads without a counter run: null.
-ATTN_TRAFFIC_BYTES = {"720p_hunyuan": (104.77e9, 0.779e9)}
+ATTN_TRAFFIC_BYTES = {"720p_hunyuan": (57.11e9, 0.754e9)}
 
 
 def cpu_baseline(w, Q, K, V, budget_s=20.0):

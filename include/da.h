@@ -133,10 +133,16 @@ int da_permute(const da_problem* p, const void* X, void* Y, int mode, void* stre
  * natural-log normaliser of each row.
  * Supported: block == 64 and (dtype, d) in {(DA_BF16, 128), (DA_F32, 64), (DA_F32, 128)};
  * anything else returns DA_ERR_UNSUPPORTED.  bf16 uses bf16 MFMA with float32 accumulation and
- * softmax (and bf16 probabilities); f32 uses float32 arithmetic throughout.  The bf16 kernel
- * keeps the block lists of four query blocks in LDS, which bounds the problem: roughly
- * g/2 + 4*min(g, 4k) bytes must fit in 32 KB (g up to about 7000 with nothing dropped, far
- * more when k << g); larger problems return DA_ERR_UNSUPPORTED.
+ * softmax (and bf16 probabilities); f32 uses float32 arithmetic throughout.
+ * The bf16 kernel leaves out, tile by tile (32 queries x 64 keys), keys whose probability is
+ * negligible: a tile is dropped when each of its scores is so far below the best score its query
+ * has met so far that everything dropped from a row adds up to less than 2^-14 of the row's largest
+ * term (the cut is log2(64 k) + 14 powers of two).  The result differs from the full sum by less
+ * than a bf16 rounding of the output; how much work is saved depends on how peaked the attention is
+ * (nothing is dropped when all scores of a row are within that range of each other).
+ * The bf16 kernel keeps the block lists of four query blocks in LDS, which bounds the problem:
+ * roughly g/2 + 4*min(g, 4k) bytes must fit in 32 KB (g up to about 7000 with nothing dropped, far
+ * more when k << g), and g < 2^22; larger problems return DA_ERR_UNSUPPORTED.
  */
 int da_sparse_attn(const da_problem* p, const void* Qp, const void* Kp, const void* Vt,
                    const int32_t* idx, void* Op, float* lse, void* stream);
@@ -145,7 +151,10 @@ int da_sparse_attn(const da_problem* p, const void* Qp, const void* Kp, const vo
  * The whole path: O = restore(SparseAttn(reorder(Q,K,V), top-k(draft logits))).
  * Q, K, V, O [B,H,N,d].  idx_out [B,H,g,k] int32 (may be NULL) receives the kept blocks.
  * ws/ws_bytes: scratch of at least da_workspace_size() bytes, 256-byte aligned.
- * Same support matrix as da_sparse_attn.
+ * Same support matrix as da_sparse_attn.  The result is that of the separate calls; the launches
+ * are fewer: K is reordered by the pooling pass, and for bf16 Q and O are never copied (the
+ * attention kernel reads query rows from, and writes output rows to, their places in the original
+ * order, which is Algorithm 1 for Q and Algorithm 2 for O done by addressing).
  */
 int da_forward(const da_problem* p, const void* Q, const void* K, const void* V, void* O,
                int32_t* idx_out, void* ws, size_t ws_bytes, void* stream);
