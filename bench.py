@@ -144,7 +144,7 @@ def main():
         ("pool+draft_logits", lambda: da.da_draft_map(p, dQ, dK, q_pool, k_pool, logits, None)),
         ("select", lambda: da.da_select_blocks(p, logits, idx, None)),
         ("reorder_qkv", lambda: (da.da_permute(p, dQ, Qp, da.DA_REORDER_ROWS), da.da_permute(p, dK, Kp, da.DA_REORDER_ROWS),
-                                 da.da_permute(p, dV, Vt, da.DA_REORDER_VT))),
+                                 da.da_permute(p, dV, Vt, da.v_layout(p.dtype)))),
         ("sparse_attn", lambda: da.da_sparse_attn(p, Qp, Kp, Vt, idx, Op, None)),
         ("restore", lambda: da.da_permute(p, Op, O, da.DA_RESTORE)),
     ]

@@ -76,8 +76,15 @@ typedef struct da_dims {
 enum {
   DA_REORDER_ROWS = 0, /* X [B,H,N,d] -> Xp [B,H,n_pad,d]; Xp[slot] = X[pi[slot]], zero rows in pad slots */
   DA_REORDER_VT = 1,   /* X [B,H,N,d] -> Xt [B,H,g,d,block]; Xt[i][c][s] = X[pi[i*block+s]][c], zeros in pad slots:
-                          the reordered tensor with every block stored transposed (what da_sparse_attn wants for V) */
-  DA_RESTORE = 2       /* Xp [B,H,n_pad,d] -> X [B,H,N,d]; X[n] = Xp[pi^-1[n]] */
+                          the reordered tensor with every block stored transposed (what da_sparse_attn wants for V
+                          with DA_F32) */
+  DA_RESTORE = 2,      /* Xp [B,H,n_pad,d] -> X [B,H,N,d]; X[n] = Xp[pi^-1[n]] */
+  DA_REORDER_VOP = 3   /* X [B,H,N,d] -> Xo [B,H,g,block*d]: the transposed block cut into the 16-byte operands of the
+                          bf16 matrix instructions, each operand group of 64 stored contiguously (what da_sparse_attn
+                          wants for V with DA_BF16).  Only for DA_BF16, block == 64 and d a multiple of 32.  With
+                          nd = d/32, 16-byte unit ((t*nd + dt)*64 + hh*32 + r) of block i holds, for e = 0..7,
+                          X[pi[i*64 + 16t + 8hh + e]][32dt + r]   (t < 4, dt < nd, hh < 2, r < 32), zeros in pad
+                          slots */
 };
 
 /* Host only, pure.  Sizes that follow from the problem (see da_dims). */
@@ -120,12 +127,12 @@ int da_draft_map(const da_problem* p, const void* Q, const void* K, float* q_poo
 int da_select_blocks(const da_problem* p, const float* scores, int32_t* idx, uint8_t* mask, void* stream);
 
 /* Reordering by pi of Algorithm 1 / restoring by pi^-1 of Algorithm 2; `mode` is one of
- * DA_REORDER_ROWS, DA_REORDER_VT, DA_RESTORE (layouts above).  Pure data movement. */
+ * DA_REORDER_ROWS, DA_REORDER_VT, DA_RESTORE, DA_REORDER_VOP (layouts above).  Pure data movement. */
 int da_permute(const da_problem* p, const void* X, void* Y, int mode, void* stream);
 
 /*
- * SparseAttn on reordered tensors.  Qp, Kp [B,H,n_pad,d] (DA_REORDER_ROWS), Vt
- * [B,H,g,d,block] (DA_REORDER_VT), idx [B,H,g,k] int32 with entries in [0,g) (any order,
+ * SparseAttn on reordered tensors.  Qp, Kp [B,H,n_pad,d] (DA_REORDER_ROWS), Vt the reordered V
+ * in the layout of its dtype (DA_REORDER_VOP for DA_BF16, DA_REORDER_VT for DA_F32), idx [B,H,g,k] int32 with entries in [0,g) (any order,
  * no repeats).  For query block i: Op[i*block+u] = sum_v softmax_v(Qp[u].Kp[v]/sqrt(d)) V[v]
  * over the valid slots v of the blocks in idx[i]; dropped blocks and pad keys get
  * probability 0.  Op [B,H,n_pad,d] in the problem's dtype; rows of pad query slots are

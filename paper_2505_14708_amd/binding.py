@@ -13,7 +13,12 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "lib", "libdraftattn.so")
 
 DA_F32, DA_BF16 = 0, 1
-DA_REORDER_ROWS, DA_REORDER_VT, DA_RESTORE = 0, 1, 2
+DA_REORDER_ROWS, DA_REORDER_VT, DA_RESTORE, DA_REORDER_VOP = 0, 1, 2, 3
+
+
+def v_layout(dtype: int) -> int:
+    """The da_permute mode that writes V the way da_sparse_attn wants it for this dtype."""
+    return DA_REORDER_VOP if dtype == DA_BF16 else DA_REORDER_VT
 DA_OK = 0
 
 EXPORTS = ["da_derive", "da_workspace_size", "da_build_perm", "da_draft_map", "da_select_blocks",

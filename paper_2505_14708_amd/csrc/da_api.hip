@@ -153,10 +153,11 @@ int da_permute(const da_problem* p, const void* X, void* Y, int mode, void* stre
   int st = check_problem(p, &q);
   if (st != DA_OK) return st;
   if (!X || !Y) return DA_ERR_NULL;
-  if (mode != DA_REORDER_ROWS && mode != DA_REORDER_VT && mode != DA_RESTORE) return DA_ERR_DIM;
+  if (mode != DA_REORDER_ROWS && mode != DA_REORDER_VT && mode != DA_RESTORE && mode != DA_REORDER_VOP) return DA_ERR_DIM;
   if (misaligned(X) || misaligned(Y)) return DA_ERR_ALIGN;
   if (!row_ok(q)) return DA_ERR_UNSUPPORTED;
   if (mode == DA_REORDER_VT && ((size_t)q.block * elem_size(q)) % 16 != 0) return DA_ERR_UNSUPPORTED;
+  if (mode == DA_REORDER_VOP && (q.dtype != DA_BF16 || q.block != 64 || q.d % 32 != 0)) return DA_ERR_UNSUPPORTED;
   return hip_status(launch_permute(q, X, Y, mode, (hipStream_t)stream));
 }
 
@@ -207,7 +208,7 @@ int da_forward(const da_problem* p, const void* Q, const void* K, const void* V,
     if ((e = launch_pool_reorder(q, Q, K, q_pool, k_pool, nullptr, kp, s)) != hipSuccess) return DA_ERR_HIP;
     if ((e = launch_draft_logits(q, q_pool, k_pool, logits, s)) != hipSuccess) return DA_ERR_HIP;
     if ((e = launch_select(q, logits, idx, nullptr, s)) != hipSuccess) return DA_ERR_HIP;
-    if ((e = launch_permute(q, V, vt, DA_REORDER_VT, s)) != hipSuccess) return DA_ERR_HIP;
+    if ((e = launch_permute(q, V, vt, DA_REORDER_VOP, s)) != hipSuccess) return DA_ERR_HIP;
     return hip_status(launch_attn_bf16_ring(q, Q, kp, vt, idx, O, nullptr, true, s));
   }
   if ((e = launch_pool_reorder(q, Q, K, q_pool, k_pool, qp, kp, s)) != hipSuccess) return DA_ERR_HIP;

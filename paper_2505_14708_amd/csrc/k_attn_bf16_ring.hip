@@ -24,7 +24,7 @@
 // accumulator registers 8t..8t+7 belong to keys 16t + 8*(l/32) + 0..7, exactly the eight
 // contraction elements the P^T operand of the second product needs, so P goes from accumulator
 // to operand without leaving the lane.  V arrives block-transposed from the reorder step, so
-// both K rows and V^T rows are read from LDS as plain 16-byte operands.
+// K rows are read from LDS, and V^T operands from global memory, as plain 16-byte pieces.
 //
 // The ring.  Eight 16 KB slots, each one K tile.  Tiles travel HBM/L2 -> LDS by 16-byte
 // direct-to-LDS loads; the lane that writes LDS position p of row r fetches global chunk
@@ -177,8 +177,9 @@ struct Soft {
 
 // One 64-key tile for one wave (32 queries).  kaddr[t] is this lane's LDS address of the K
 // operand of k-step t (swizzle already applied; the second 32 keys sit 8 KB further).  vt is
-// this lane's part of the tile's V^T in global memory: channel row r, 16-byte chunk hh; the
-// operand of (k-step t, channel group dt) is 32t bytes and 32dt rows further.
+// this lane's 16 bytes of the first operand group of the tile's V^T in global memory (operand
+// order: the 64 lanes' operands of (k-step t, channel group dt) are the contiguous KB number
+// 4t + dt of the tile, so every load of a wave is one contiguous KB).
 __device__ __forceinline__ void compute_tile(const unsigned char* const (&kaddr)[8], const unsigned char* vt, int hh,
                                              int nv, bool pad_query, float skip, const bf16x8 (&qf)[8], f32x16 (&o)[4], Soft& st) {
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -216,7 +217,7 @@ __device__ __forceinline__ void compute_tile(const unsigned char* const (&kaddr)
 #pragma unroll
   for (int t = 0; t < 4; ++t)
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) va[t][dt] = *(const bf16x8*)(vt + dt * (32 * 128) + t * 32);
+    for (int dt = 0; dt < 4; ++dt) va[t][dt] = *(const bf16x8*)(vt + (t * 4 + dt) * 1024);
   st.top = fmaxf(st.top, mx);
   if (__any((mx - st.m) * kC2 > kLazy)) {
     const float m_new = fmaxf(st.m, mx);
@@ -450,7 +451,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   unsigned koff[4];
   tile_lane_offsets<256>(lane, koff);
   const unsigned char* Kbh = Kp + bh * q.n_pad * (D * 2);
-  const unsigned char* Vlane = Vt + bh * q.n_pad * (D * 2) + r * 128 + hh * 16;
+  const unsigned char* Vlane = Vt + bh * q.n_pad * (D * 2) + lane * 16;
   // one wave brings the K tile of union entry u into ring slot u % RING
   auto issue_tile = [&](int u) {
     const unsigned e = ulist[u];

@@ -57,7 +57,10 @@ __global__ __launch_bounds__(256) void permute_rows_kernel(Geo q, const chunk16*
 
 // Block-transposed reorder: Xt[bh][i][c][s] = X[bh][pi[i*block+s]][c] (zeros in pad slots).
 // One workgroup per (block, batch*head).  The block's rows go through LDS; ES = element bytes.
-template <typename E>
+// OPERAND (bf16, block 64, d a multiple of 32): the same transposed block, written as the 16-byte
+// operands of the matrix instructions: unit ((t*nd + dt)*64 + hh*32 + r) holds channel 32dt + r,
+// slots 16t + 8hh + 0..7.
+template <typename E, bool OPERAND>
 __global__ __launch_bounds__(256) void permute_vt_kernel(Geo q, const E* __restrict__ X, E* __restrict__ Y) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int PER = 16 / sizeof(E);  // elements per 16-byte chunk
@@ -80,8 +83,21 @@ __global__ __launch_bounds__(256) void permute_vt_kernel(Geo q, const E* __restr
     *(chunk16*)(tile + s * ld + c * PER) = val;
   }
   __syncthreads();
-  int spr = q.block / PER;  // 16-byte chunks per output row (a row holds `block` slots of one channel)
   E* out = Y + (bh * q.g + i) * (long long)q.d * q.block;
+  if (OPERAND) {
+    const int nd = q.d >> 5;
+    for (int e = threadIdx.x; e < q.d * q.block / PER; e += blockDim.x) {
+      const int r = e & 31, hh = (e >> 5) & 1, grp = e >> 6;
+      const int t = grp / nd, dt = grp - t * nd;
+      const int c = 32 * dt + r, s0 = 16 * t + 8 * hh;
+      E tmp[PER];
+#pragma unroll
+      for (int j = 0; j < PER; ++j) tmp[j] = tile[(s0 + j) * ld + c];
+      *(chunk16*)(out + (long long)e * PER) = *(chunk16*)tmp;
+    }
+    return;
+  }
+  int spr = q.block / PER;  // 16-byte chunks per output row (a row holds `block` slots of one channel)
   for (int e = threadIdx.x; e < q.d * spr; e += blockDim.x) {
     int c = e / spr, s8 = e - c * spr;
     E tmp[PER];
@@ -109,10 +125,12 @@ hipError_t launch_permute(const Geo& q, const void* X, void* Y, int mode, hipStr
     size_t per = 16 / es;
     size_t lds = (size_t)q.block * (q.d + per) * es;
     if (lds > 64 * 1024) return hipErrorInvalidValue;
-    if (es == 2)
-      hipLaunchKernelGGL(permute_vt_kernel<uint16_t>, grid, dim3(256), lds, s, q, (const uint16_t*)X, (uint16_t*)Y);
+    if (mode == DA_REORDER_VOP)
+      hipLaunchKernelGGL((permute_vt_kernel<uint16_t, true>), grid, dim3(256), lds, s, q, (const uint16_t*)X, (uint16_t*)Y);
+    else if (es == 2)
+      hipLaunchKernelGGL((permute_vt_kernel<uint16_t, false>), grid, dim3(256), lds, s, q, (const uint16_t*)X, (uint16_t*)Y);
     else
-      hipLaunchKernelGGL(permute_vt_kernel<uint32_t>, grid, dim3(256), lds, s, q, (const uint32_t*)X, (uint32_t*)Y);
+      hipLaunchKernelGGL((permute_vt_kernel<uint32_t, false>), grid, dim3(256), lds, s, q, (const uint32_t*)X, (uint32_t*)Y);
   }
   return hipGetLastError();
 }

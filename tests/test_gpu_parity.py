@@ -11,7 +11,7 @@ from oracle import draft_attention as oa
 from paper_2505_14708_amd import binding as da
 from paper_2505_14708_amd import workloads as W
 from gpu_util import (HeadRef, TOL, empty, output_error, say, stratified_rows, to_dev, to_host_f64,
-                      to_host_storage, vt_to_rows)
+                      to_host_storage, vop_to_rows, vt_to_rows)
 
 pytestmark = pytest.mark.gpu
 
@@ -90,6 +90,14 @@ def test_permute_bit_exact(torch_mod, cases, name):
         assert np.array_equal(vt_to_rows(hvt[b, h], dims.g, w.d, dims.block), want)
         assert np.array_equal(hback[b, h], oa.restore(want, ref.inv))
     assert np.array_equal(hback, V)          # restore(reorder(X)) == X
+    if w.dtype == W.BF16 and dims.block == 64 and w.d % 32 == 0:
+        vo = empty((w.B, w.H, dims.g, dims.block * w.d), w.dtype)
+        vo.fill_(7.0)
+        da.da_permute(p, x, vo, da.DA_REORDER_VOP)
+        torch.cuda.synchronize()
+        hvo = to_host_storage(vo, w.dtype)
+        for (b, h), ref in refs.items():
+            assert np.array_equal(vop_to_rows(hvo[b, h], dims.g, w.d), oa.permute(V[b, h], ref.perm))
 
 
 def test_permute_other_windows(torch_mod):
@@ -238,7 +246,7 @@ def _attn_inputs(torch, w, Q, K, V, refs, idx_np):
     Vt = empty((w.B, w.H, dims.g, w.d, dims.block), w.dtype)
     da.da_permute(p, to_dev(Q, w.dtype), Qp, da.DA_REORDER_ROWS)
     da.da_permute(p, to_dev(K, w.dtype), Kp, da.DA_REORDER_ROWS)
-    da.da_permute(p, to_dev(V, w.dtype), Vt, da.DA_REORDER_VT)
+    da.da_permute(p, to_dev(V, w.dtype), Vt, da.v_layout(w.dtype))
     idx = torch.from_numpy(idx_np.astype(np.int32)).cuda()
     return p, dims, Qp, Kp, Vt, idx
 
