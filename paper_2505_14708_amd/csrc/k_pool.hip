@@ -32,11 +32,13 @@ struct Vec<DA_F32> {
   }
 };
 
+constexpr int kPoolThreads = 64;
+
 // grid.x covers (bh, block, chunk) items; grid.y = 0 for Q, 1 for K.  With REORDER the tokens are
 // also written, as they go by, to their slots of the reordered tensors Qp, Kp (Algorithm 1), pad
 // slots zeroed: pooling and reordering then read Q and K once between them.
 template <int DT, bool REORDER>
-__global__ __launch_bounds__(256) void pool_kernel(Geo q, const uint4* __restrict__ Q, const uint4* __restrict__ K,
+__global__ __launch_bounds__(kPoolThreads) void pool_kernel(Geo q, const uint4* __restrict__ Q, const uint4* __restrict__ K,
                                                    float* __restrict__ q_pool, float* __restrict__ k_pool,
                                                    uint4* __restrict__ Qp, uint4* __restrict__ Kp, int cpr,
                                                    long long items) {
@@ -57,7 +59,26 @@ __global__ __launch_bounds__(256) void pool_kernel(Geo q, const uint4* __restric
   float acc[N];
 #pragma unroll
   for (int j = 0; j < N; ++j) acc[j] = 0.f;
-  for (int u = 0; u < b.vh; ++u) {
+  int u = 0;
+  // two full patch rows at a time where the patch is 8 wide: sixteen independent loads in flight,
+  // added in slot order
+  if (b.vw == 8) {
+    for (; u + 2 <= b.vh; u += 2) {
+      const uint4* row = src + (long long)u * q.fw * cpr;
+      uint4 r[16];
+#pragma unroll
+      for (int t = 0; t < 16; ++t) r[t] = row[((long long)(t >> 3) * q.fw + (t & 7)) * cpr];
+#pragma unroll
+      for (int t = 0; t < 16; ++t) {
+        if (wr) dstp[(long long)(u * 8 + t) * cpr] = r[t];
+        float f[N];
+        Vec<DT>::widen(r[t], f);
+#pragma unroll
+        for (int j = 0; j < N; ++j) acc[j] = acc[j] + f[j];
+      }
+    }
+  }
+  for (; u < b.vh; ++u) {
     const uint4* row = src + (long long)u * q.fw * cpr;
     int v = 0;
     for (; v + 8 <= b.vw; v += 8) {  // eight independent loads in flight, added in order
@@ -100,11 +121,11 @@ hipError_t launch_pool_reorder(const Geo& q, const void* Q, const void* K, float
   size_t es = q.dtype == DA_BF16 ? 2 : 4;
   int cpr = (int)(q.d * es / 16);
   long long items = (long long)q.B * q.H * q.g * cpr;
-  dim3 grid((unsigned)((items + 255) / 256), 2);
+  dim3 grid((unsigned)((items + kPoolThreads - 1) / kPoolThreads), 2);
   const bool re = Qp != nullptr || Kp != nullptr;
 #define DA_POOL_LAUNCH(DT, RE)                                                                                        \
-  hipLaunchKernelGGL((pool_kernel<DT, RE>), grid, dim3(256), 0, s, q, (const uint4*)Q, (const uint4*)K, q_pool, k_pool, \
-                     (uint4*)Qp, (uint4*)Kp, cpr, items)
+  hipLaunchKernelGGL((pool_kernel<DT, RE>), grid, dim3(kPoolThreads), 0, s, q, (const uint4*)Q, (const uint4*)K, q_pool, \
+                     k_pool, (uint4*)Qp, (uint4*)Kp, cpr, items)
   if (q.dtype == DA_BF16) {
     if (re) DA_POOL_LAUNCH(DA_BF16, true); else DA_POOL_LAUNCH(DA_BF16, false);
   } else {
