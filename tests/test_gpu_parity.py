@@ -306,6 +306,51 @@ def test_sparse_attn_list_order_and_dense_case(torch_mod, cases):
     assert emax <= 2e-2 and emean <= 2e-3
 
 
+@pytest.mark.parametrize("profile", ["rising", "falling", "spike", "flat"])
+def test_sparse_attn_score_profiles(torch_mod, cases, profile):
+    """The bf16 kernel drops tiles whose probabilities are negligible next to the best score a query
+    has met so far.  Key blocks scaled so that the scores rise along the walk (the best comes last,
+    nothing may be dropped wrongly before it), fall (most tiles are dropped), have one dominating
+    block, or are all alike (nothing is dropped); every block kept, so the oracle is full attention."""
+    torch = torch_mod
+    w, Q, K, V, refs = cases["bf16_480p_T3"]
+    ref = refs[(0, 0)]
+    g = ref.dims["g"]
+    say(f"sparse_attn score profile {profile}")
+    blk = ref.inv // 64                                   # block of every token
+    kf = oa.widen_f64(K[0, 0], w.dtype)
+    qf = oa.widen_f64(Q[0, 0], w.dtype)
+    if profile == "rising":
+        gain = 0.2 + 1.8 * blk / (g - 1)
+    elif profile == "falling":
+        gain = 2.0 - 1.8 * blk / (g - 1)
+    elif profile == "spike":
+        gain = np.where(blk == g // 2, 3.0, 0.3)
+    else:
+        gain = np.full(blk.shape, 0.02)
+    K2 = W.to_storage(kf * gain[:, None], w.dtype)
+    Q2 = W.to_storage(qf, w.dtype)
+    w1 = w.with_(H=1, sparsity=0.0)
+    p = da.problem_of(w1)
+    dims = da.da_derive(p)
+    assert dims.k == g
+    Qp = empty((1, 1, dims.n_pad, w.d), w.dtype)
+    Kp = empty((1, 1, dims.n_pad, w.d), w.dtype)
+    Vt = empty((1, 1, dims.g, w.d, dims.block), w.dtype)
+    Op = empty((1, 1, dims.n_pad, w.d), w.dtype)
+    da.da_permute(p, to_dev(Q2[None, None], w.dtype), Qp, da.DA_REORDER_ROWS)
+    da.da_permute(p, to_dev(K2[None, None], w.dtype), Kp, da.DA_REORDER_ROWS)
+    da.da_permute(p, to_dev(V[:, :1], w.dtype), Vt, da.v_layout(w.dtype))
+    idx_all = torch.arange(g, dtype=torch.int32, device="cuda").repeat(g, 1).contiguous()
+    da.da_sparse_attn(p, Qp, Kp, Vt, idx_all, Op, None)
+    torch.cuda.synchronize()
+    full = oa.full_attention(oa.widen_f64(Q2, w.dtype), oa.widen_f64(K2, w.dtype), oa.widen_f64(V[0, 0], w.dtype))
+    got = oa.restore(to_host_f64(Op, w.dtype)[0, 0], ref.inv)
+    emax, emean = output_error(got, full)
+    say(f"  {profile}: max-abs {emax:.3e} mean-abs {emean:.3e}")
+    assert emax <= 2e-2 and emean <= 2e-3
+
+
 def test_sparse_attn_deterministic(torch_mod, cases):
     """Two launches give the same bits (the ring's request order varies from run to run, the
     arithmetic of a query block does not)."""
