@@ -149,7 +149,8 @@ int da_permute(const da_problem* p, const void* X, void* Y, int mode, void* stre
  * (nothing is dropped when all scores of a row are within that range of each other).
  * The bf16 kernel keeps the block lists of four query blocks in LDS, which bounds the problem:
  * roughly g/2 + 4*min(g, 4k) bytes must fit in 32 KB (g up to about 7000 with nothing dropped, far
- * more when k << g), and g < 2^22; larger problems return DA_ERR_UNSUPPORTED.
+ * more when k << g), and g < 2^22; larger problems return DA_ERR_UNSUPPORTED.  Its waits for tiles are
+ * bounded; should one ever run out (no valid input makes it), the rows concerned are written as NaN.
  */
 int da_sparse_attn(const da_problem* p, const void* Qp, const void* Kp, const void* Vt,
                    const int32_t* idx, void* Op, float* lse, void* stream);

@@ -37,7 +37,7 @@
 //              whichever wave notices first claims it with a compare-and-swap, waits for the load
 //              at the top of its next trip (or while it is idle) and publishes it.
 // A wave reads all of this with one LDS access per poll.  Every wait is bounded: if a tile does
-// not show up the wave gives up (its output is then wrong, but the kernel always ends).
+// not show up the wave gives up (its output rows are then NaN, but the kernel always ends).
 //
 // V does not go through LDS.  After S = QK^T of a tile a wave knows the largest score of each of
 // its queries; when every score of the tile is so far below the best the query has seen that
@@ -620,6 +620,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
         bf16x2 b0 = __builtin_convertvector(v0, bf16x2);
         bf16x2 b1 = __builtin_convertvector(v1, bf16x2);
         uint2 w2 = make_uint2(*(unsigned*)&b0, *(unsigned*)&b1);
+        if (gave_up) w2 = make_uint2(0x7fc07fc0u, 0x7fc07fc0u);   // a wait ran out: say so with NaN rather than with wrong numbers
         *(uint2*)(stage + r * O_STRIDE + (32 * dt + 8 * a + 4 * hh) * 2) = w2;
       }
   }
