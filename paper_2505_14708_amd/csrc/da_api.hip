@@ -52,9 +52,8 @@ inline size_t elem_size(const Geo& q) { return q.dtype == DA_BF16 ? 2 : 4; }
 inline bool row_ok(const Geo& q) { return ((size_t)q.d * elem_size(q)) % 16 == 0; }
 
 inline bool attn_supported(const Geo& q) {
-  if (q.block != 64) return false;
-  if (q.dtype == DA_BF16) return q.d == 128 && attn_bf16_ring_fits(q) != 0;
-  return q.d == 64 || q.d == 128;
+  if (q.dtype == DA_BF16) return (q.block == 64 || q.block == 128) && q.d == 128 && attn_bf16_ring_fits(q) != 0;
+  return q.block == 64 && (q.d == 64 || q.d == 128);
 }
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -157,7 +156,7 @@ int da_permute(const da_problem* p, const void* X, void* Y, int mode, void* stre
   if (misaligned(X) || misaligned(Y)) return DA_ERR_ALIGN;
   if (!row_ok(q)) return DA_ERR_UNSUPPORTED;
   if (mode == DA_REORDER_VT && ((size_t)q.block * elem_size(q)) % 16 != 0) return DA_ERR_UNSUPPORTED;
-  if (mode == DA_REORDER_VOP && (q.dtype != DA_BF16 || q.block != 64 || q.d % 32 != 0)) return DA_ERR_UNSUPPORTED;
+  if (mode == DA_REORDER_VOP && (q.dtype != DA_BF16 || q.block % 64 != 0 || q.d % 32 != 0)) return DA_ERR_UNSUPPORTED;
   return hip_status(launch_permute(q, X, Y, mode, (hipStream_t)stream));
 }
 

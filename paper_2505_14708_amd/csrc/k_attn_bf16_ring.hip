@@ -279,6 +279,10 @@ __device__ __forceinline__ bool compute_tile(const unsigned char* const (&kaddr)
   return true;
 }
 
+// SUB = 64-token sub-blocks per block (1: 8x8 patches, 2: 128-token blocks such as 8x16 patches).  A block of
+// 128 is two K tiles and two V tiles in a row, and its queries are four waves' worth: the workgroup then takes two
+// query blocks (two consecutive frames) instead of four, and a key block enters the union walk as two entries.
+template <int SUB>
 __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const unsigned char* __restrict__ Qp,
                                                                const unsigned char* __restrict__ Kp,
                                                                const unsigned char* __restrict__ Vt,
@@ -289,11 +293,13 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   // Heads one after the other (the K/V of the heads in flight then fit the last-level cache);
-  // inside a head a workgroup is one patch position and four consecutive frames, and the frame
+  // inside a head a workgroup is one patch position and FG consecutive frames, and the frame
   // groups of one position follow each other on one XCD (workgroups are dealt round-robin to the
   // 8 XCDs).
+  constexpr int FG = 4 / SUB;                         // query blocks (frames) per workgroup
+  constexpr int BLOCK = BS * SUB;                     // slots per block
   const int per_frame = q.gh * q.gw;
-  const int fgs = (q.T + 3) >> 2;
+  const int fgs = (q.T + FG - 1) / FG;
   const int pos_per_xcd = (per_frame + 7) >> 3;
   const int wg_per_head = 8 * pos_per_xcd * fgs;
   const long long bh = blockIdx.x / wg_per_head;
@@ -301,10 +307,11 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   const int xcd = n & 7, slot_id = n >> 3;
   const int pos = xcd + 8 * (slot_id / fgs);
   if (pos >= per_frame) return;                       // the whole workgroup leaves together
-  // waves w and w+4 share a SIMD: give them different query blocks
+  // waves w and w+4 share a SIMD: give them different query blocks.  part = which 32 queries of the block.
   const int half = wave >> 2;
-  const int qblk = (wave + 2 * half) & 3;
-  const int f = 4 * (slot_id % fgs) + qblk;
+  const int qblk = SUB == 1 ? (wave + 2 * half) & 3 : half;
+  const int part = SUB == 1 ? half : wave & 3;
+  const int f = FG * (slot_id % fgs) + qblk;
   const bool live = f < q.T;                          // a wave past the last frame only helps with the ring
   const long long qb = bh * q.g + (long long)min(f, q.T - 1) * per_frame + pos;
   const int k = q.k, g = q.g;
@@ -316,7 +323,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   const BlockPos qpos = block_pos(q, (int)(min(f, q.T - 1) * per_frame + pos));
   // row of slot s of my query block in Qp / Op, or -1 (pad slot of the original order)
   auto row_of = [&](int s) -> long long {
-    if (!direct) return qb * BS + s;
+    if (!direct) return qb * BLOCK + s;
     if (s >= qpos.vh * qpos.vw) return -1;
     const int u = s / qpos.vw, v = s - u * qpos.vw;
     return bh * q.n + ((long long)qpos.f * q.fh + qpos.y0 + u) * q.fw + qpos.x0 + v;
@@ -324,7 +331,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   bf16x8 qf[8];
   {
     const int r = lane & 31, hh = lane >> 5;
-    const long long row = row_of(32 * half + r);
+    const long long row = row_of(32 * part + r);
     const unsigned char* qrow = Qp + max(row, 0LL) * (D * 2);
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
@@ -336,21 +343,21 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
     }
   }
 
-  unsigned* bitmap = (unsigned*)(smem + RING_BYTES);  // [4][bw] one bitmap of kept key blocks per query block
+  unsigned* bitmap = (unsigned*)(smem + RING_BYTES);  // [FG][bw] one bitmap of kept key blocks per query block
   const int bw = (g + 31) >> 5;
-  unsigned* ulist = bitmap + 4 * bw;                  // union entries: key block | (valid slots - 1) << 22 | membership << 28
-  const int union_max = min(g, 4 * k);
+  unsigned* ulist = bitmap + 4 * bw;                  // union entries: key sub-block | (valid slots - 1) << 22 | membership << 28
+  const int union_max = SUB * min(g, FG * k);
   int* ctrl = (int*)(smem + LDS_TOTAL - 128);         // [32]: ready[8], prog[8], next_load, count, n_own
   int* ready = ctrl;                                  // [RING]
   int* prog = ctrl + 8;                               // [WAVES]
   int* next_load = ctrl + 16;
   int* count = ctrl + 17;                             // [2]
 
-  // ---- union of the four lists
+  // ---- union of the workgroup's lists
   for (int i = threadIdx.x; i < 4 * bw; i += 512) bitmap[i] = 0u;
   if (threadIdx.x < 32) ctrl[threadIdx.x] = threadIdx.x < RING ? -1 : 0;
   __syncthreads();
-  if (live && half == 0) {
+  if (live && part == 0) {
     const int32_t* list = idx + qb * k;
     for (int e = lane; e < k; e += 64) {
       int j = list[e];
@@ -358,23 +365,30 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
     }
   }
   __syncthreads();
-  // The workgroup's own four blocks go first (when kept): a query's best scores tend to be
+  // The workgroup's own blocks go first (when kept): a query's best scores tend to be
   // there, and the sooner the running maximum is near its final value, the more of the other
   // tiles turn out negligible.
-  const int own_lo = (4 * (slot_id % fgs)) * per_frame + pos;   // own blocks: own_lo + w * per_frame, w = 0..3
-  // membership of key block j in the four lists (0 for the own blocks unless asked for)
+  const int own_lo = (FG * (slot_id % fgs)) * per_frame + pos;   // own blocks: own_lo + w * per_frame, w < FG
+  // membership of key block j in the workgroup's lists (0 for the own blocks unless asked for)
   auto membership = [&](int j, bool want_own) -> unsigned {
     const int dj = j - own_lo;
-    const bool own = dj >= 0 && dj < 4 * per_frame && dj % per_frame == 0;
+    const bool own = dj >= 0 && dj < FG * per_frame && dj % per_frame == 0;
     unsigned m4 = 0;
     if (j < g && own == want_own) {
 #pragma unroll
-      for (int w = 0; w < 4; ++w) m4 |= ((bitmap[w * bw + (j >> 5)] >> (j & 31)) & 1u) << w;
+      for (int w = 0; w < FG; ++w) m4 |= ((bitmap[w * bw + (j >> 5)] >> (j & 31)) & 1u) << w;
     }
     return m4;
   };
-  auto entry_of = [&](int j, unsigned m4) -> unsigned {
-    return (unsigned)j | ((unsigned)(valid_slots(q, per_frame, j) - 1) << 22) | (m4 << 28);
+  // a key block becomes one entry per 64-slot sub-block that holds a valid slot (in a row)
+  auto second = [&](int j) -> bool { return SUB == 2 && j < g && valid_slots(q, per_frame, j) > BS; };
+  auto put_entries = [&](int at, int j, unsigned m4, bool two) {
+    const int nvb = valid_slots(q, per_frame, j);
+    ulist[at] = (unsigned)(j * SUB) | ((unsigned)(min(nvb, BS) - 1) << 22) | (m4 << 28);
+    if (two) ulist[at + 1] = (unsigned)(j * SUB + 1) | ((unsigned)(nvb - BS - 1) << 22) | (m4 << 28);
+  };
+  auto lanes_before = [&](unsigned long long m) -> int {
+    return __builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0));
   };
   // every wave takes a contiguous eighth of the key blocks, 64 at a time: count, then place
   int* wcount = ctrl + 20;                            // [WAVES]
@@ -382,14 +396,19 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   const int c_lo = wave * cpw, c_hi = min(chunks, c_lo + cpw);
   {
     int cnt = 0;
-    for (int c = c_lo; c < c_hi; ++c) cnt += __popcll(__ballot(membership(c * 64 + lane, false) != 0u));
+    for (int c = c_lo; c < c_hi; ++c) {
+      const int j = c * 64 + lane;
+      const bool in = membership(j, false) != 0u;
+      cnt += __popcll(__ballot(in)) + (SUB == 2 ? __popcll(__ballot(in && second(j))) : 0);
+    }
     if (lane == 0) wcount[wave] = cnt;
     if (wave == 0) {
-      const unsigned m4 = lane < 4 ? membership(own_lo + lane * per_frame, true) : 0u;
-      const unsigned long long nz = __ballot(m4 != 0u);
-      const int before = __builtin_amdgcn_mbcnt_hi((unsigned)(nz >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)nz, 0));
-      if (m4) ulist[before] = entry_of(own_lo + lane * per_frame, m4);
-      if (lane == 0) count[1] = __popcll(nz);
+      const int j = own_lo + lane * per_frame;
+      const unsigned m4 = lane < FG ? membership(j, true) : 0u;
+      const bool two = m4 != 0u && second(j);
+      const unsigned long long nz = __ballot(m4 != 0u), n2 = __ballot(two);
+      if (m4) put_entries(lanes_before(nz) + lanes_before(n2), j, m4, two);
+      if (lane == 0) count[1] = __popcll(nz) + __popcll(n2);
     }
   }
   __syncthreads();
@@ -399,10 +418,10 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
     for (int c = c_lo; c < c_hi; ++c) {
       const int j = c * 64 + lane;
       const unsigned m4 = membership(j, false);
-      const unsigned long long nz = __ballot(m4 != 0u);
-      const int before = __builtin_amdgcn_mbcnt_hi((unsigned)(nz >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)nz, 0));
-      if (m4) ulist[at + before] = entry_of(j, m4);
-      at += __popcll(nz);
+      const bool two = m4 != 0u && second(j);
+      const unsigned long long nz = __ballot(m4 != 0u), n2 = __ballot(two);
+      if (m4) put_entries(at + lanes_before(nz) + lanes_before(n2), j, m4, two);
+      at += __popcll(nz) + __popcll(n2);
     }
     if (wave == WAVES - 1 && lane == 0) count[0] = at;
   }
@@ -522,7 +541,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   for (int t = 0; t < 8; ++t) asm volatile("" : "+v"(qf[t]));
 
   const unsigned my_bit = live ? (1u << (28 + qblk)) : 0u;
-  const bool pad_query = 32 * half + r >= valid_slots(q, per_frame, pos);
+  const bool pad_query = 32 * part + r >= valid_slots(q, per_frame, pos);
   // a look at the whole control block: lane i holds ctrl[i]
   auto look = [&]() -> int { return __atomic_load_n(ctrl + (lane & 31), __ATOMIC_RELAXED); };
   // request the next tile if the ring has room, judging by a look c (which may be old: then the
@@ -609,7 +628,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   {
     const float lt = sum_across_halves(st.l);
     const float inv = lt > 0.f ? 1.0f / lt : 0.f;     // 0 only in pad query slots whose wave skipped every tile
-    if (lse && hh == 0) lse[qb * BS + 32 * half + r] = st.m * kScale + __logf(lt);
+    if (lse && hh == 0) lse[qb * BLOCK + 32 * part + r] = st.m * kScale + __logf(lt);
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -629,7 +648,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
 #pragma unroll
   for (int it = 0; it < 8; ++it) {
     const int row = it * 4 + (lane >> 4), ch = lane & 15;
-    const long long orow = row_of(32 * half + row);
+    const long long orow = row_of(32 * part + row);
     if (orow >= 0) *(uint4*)(Op + orow * (D * 2) + ch * 16) = *(const uint4*)(stage + row * O_STRIDE + ch * 16);
   }
 }
@@ -640,8 +659,10 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
 // and, for the balanced walk, two more arrays of that length.
 // 0: the kernel cannot run this problem; 1: it can, walking in ascending order; 2: balanced walk.
 int attn_bf16_ring_fits(const Geo& q) {
-  if (q.g >= (1 << 22)) return 0;
-  long long union_max = (long long)q.g < 4LL * q.k ? q.g : 4LL * q.k;
+  if (q.block != ring::BS && q.block != 2 * ring::BS) return 0;
+  const int sub = q.block / ring::BS, fg = 4 / sub;
+  if ((long long)q.g * sub >= (1 << 22)) return 0;
+  long long union_max = sub * ((long long)q.g < (long long)fg * q.k ? q.g : (long long)fg * q.k);
   long long base = 4LL * 4 * ((q.g + 31) / 32) + 4 * union_max + 512;
   if (base > ring::AUX_BYTES) return 0;
   return base + 8 * union_max <= ring::AUX_BYTES ? 2 : 1;
@@ -650,10 +671,18 @@ int attn_bf16_ring_fits(const Geo& q) {
 hipError_t launch_attn_bf16_ring(const Geo& q, const void* Qp, const void* Kp, const void* Vt, const int32_t* idx,
                                  void* Op, float* lse, bool direct, hipStream_t s) {
   const int per_frame = q.gh * q.gw;
-  unsigned grid = (unsigned)((long long)q.B * q.H * 8 * ((per_frame + 7) / 8) * ((q.T + 3) / 4));
-  hipLaunchKernelGGL(ring::attn_bf16_ring_kernel, dim3(grid), dim3(512), 0, s, q, (const unsigned char*)Qp,
-                     (const unsigned char*)Kp, (const unsigned char*)Vt, idx, (unsigned char*)Op, lse,
-                     attn_bf16_ring_fits(q) == 2 ? 1 : 0, log2f((float)q.k * (float)ring::BS) + ring::kDropLog2, direct ? 1 : 0);
+  const int sub = q.block / ring::BS, fg = 4 / sub;
+  unsigned grid = (unsigned)((long long)q.B * q.H * 8 * ((per_frame + 7) / 8) * ((q.T + fg - 1) / fg));
+  const int balance = attn_bf16_ring_fits(q) == 2 ? 1 : 0;
+  const float skip = log2f((float)q.k * (float)q.block) + ring::kDropLog2;
+  if (sub == 1)
+    hipLaunchKernelGGL(ring::attn_bf16_ring_kernel<1>, dim3(grid), dim3(512), 0, s, q, (const unsigned char*)Qp,
+                       (const unsigned char*)Kp, (const unsigned char*)Vt, idx, (unsigned char*)Op, lse, balance, skip,
+                       direct ? 1 : 0);
+  else
+    hipLaunchKernelGGL(ring::attn_bf16_ring_kernel<2>, dim3(grid), dim3(512), 0, s, q, (const unsigned char*)Qp,
+                       (const unsigned char*)Kp, (const unsigned char*)Vt, idx, (unsigned char*)Op, lse, balance, skip,
+                       direct ? 1 : 0);
   return hipGetLastError();
 }
 

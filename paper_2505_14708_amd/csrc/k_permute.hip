@@ -57,9 +57,9 @@ __global__ __launch_bounds__(256) void permute_rows_kernel(Geo q, const chunk16*
 
 // Block-transposed reorder: Xt[bh][i][c][s] = X[bh][pi[i*block+s]][c] (zeros in pad slots).
 // One workgroup per (block, batch*head).  The block's rows go through LDS; ES = element bytes.
-// OPERAND (bf16, block 64, d a multiple of 32): the same transposed block, written as the 16-byte
-// operands of the matrix instructions: unit ((t*nd + dt)*64 + hh*32 + r) holds channel 32dt + r,
-// slots 16t + 8hh + 0..7.
+// OPERAND (bf16, block a multiple of 64, d a multiple of 32): the same transposed block, written as
+// the 16-byte operands of the matrix instructions, one 64-slot sub-block after the other: unit
+// ((t*nd + dt)*64 + hh*32 + r) of sub-block sb holds channel 32dt + r, slots 64sb + 16t + 8hh + 0..7.
 template <typename E, bool OPERAND>
 __global__ __launch_bounds__(256) void permute_vt_kernel(Geo q, const E* __restrict__ X, E* __restrict__ Y) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -85,11 +85,12 @@ __global__ __launch_bounds__(256) void permute_vt_kernel(Geo q, const E* __restr
   __syncthreads();
   E* out = Y + (bh * q.g + i) * (long long)q.d * q.block;
   if (OPERAND) {
-    const int nd = q.d >> 5;
+    const int nd = q.d >> 5, per_half = q.d * 64 / PER;   // 16-byte units per 64-slot sub-block
     for (int e = threadIdx.x; e < q.d * q.block / PER; e += blockDim.x) {
-      const int r = e & 31, hh = (e >> 5) & 1, grp = e >> 6;
+      const int sb = e / per_half, eh = e - sb * per_half;
+      const int r = eh & 31, hh = (eh >> 5) & 1, grp = eh >> 6;
       const int t = grp / nd, dt = grp - t * nd;
-      const int c = 32 * dt + r, s0 = 16 * t + 8 * hh;
+      const int c = 32 * dt + r, s0 = 64 * sb + 16 * t + 8 * hh;
       E tmp[PER];
 #pragma unroll
       for (int j = 0; j < PER; ++j) tmp[j] = tile[(s0 + j) * ld + c];

@@ -49,15 +49,16 @@ def vt_to_rows(vt: np.ndarray, g: int, d: int, block: int) -> np.ndarray:
     return np.swapaxes(x, -1, -2).reshape(lead + (g * block, d))
 
 
-def vop_to_rows(vo: np.ndarray, g: int, d: int) -> np.ndarray:
-    """DA_REORDER_VOP layout (64-slot blocks, 16-byte units of 8 bf16) -> [.., g*64, d] rows: unit
-    ((t*nd + dt)*64 + hh*32 + r) holds channel 32dt + r of slots 16t + 8hh + 0..7."""
-    lead = vo.shape[:-2]                                   # vo is [.., g, 64*d]
-    nd = d // 32
-    x = vo.reshape(lead + (g, 4, nd, 2, 32, 8))            # [g, t, dt, hh, r, e]
+def vop_to_rows(vo: np.ndarray, g: int, d: int, block: int = 64) -> np.ndarray:
+    """DA_REORDER_VOP layout (16-byte units of 8 bf16, one 64-slot sub-block after the other) ->
+    [.., g*block, d] rows: unit ((t*nd + dt)*64 + hh*32 + r) of sub-block sb holds channel 32dt + r
+    of slots 64sb + 16t + 8hh + 0..7."""
+    lead = vo.shape[:-2]                                   # vo is [.., g, block*d]
+    nd, sub = d // 32, block // 64
+    x = vo.reshape(lead + (g * sub, 4, nd, 2, 32, 8))      # [g*sub, t, dt, hh, r, e]
     nl = len(lead)
-    x = np.moveaxis(x, [nl + 1, nl + 3, nl + 5, nl + 2, nl + 4], [nl + 1, nl + 2, nl + 3, nl + 4, nl + 5])   # [g, t, hh, e, dt, r]
-    return x.reshape(lead + (g * 64, d))
+    x = np.moveaxis(x, [nl + 1, nl + 3, nl + 5, nl + 2, nl + 4], [nl + 1, nl + 2, nl + 3, nl + 4, nl + 5])   # [.., t, hh, e, dt, r]
+    return x.reshape(lead + (g * block, d))
 
 
 class HeadRef:

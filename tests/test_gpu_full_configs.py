@@ -61,7 +61,7 @@ def test_full_config(name, heads, check):
         got = to_host_f64(O[0, i], w.dtype)
         worst = (0.0, 0.0)
         for r in rows:
-            slots = np.arange(r * 64, r * 64 + ref.valid[r])
+            slots = np.arange(r * dims.block, r * dims.block + ref.valid[r])
             toks = ref.perm[slots]
             emax, emean = output_error(got[toks], want[slots])
             worst = (max(worst[0], emax), max(worst[1], emean))

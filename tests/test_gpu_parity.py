@@ -21,6 +21,10 @@ SMALL = {
     "bf16_720p_T2": W.CONFIGS["720p_hunyuan"].with_(name="bf16_720p_T2", H=2, T=2, sparsity=0.9),
     "f32_ragged": W.Workload("f32_ragged", B=2, H=1, d=64, T=2, fh=20, fw=12, sparsity=0.4, dtype=W.F32, seed=3),
     "bf16_one_block": W.Workload("bf16_one_block", B=1, H=1, d=128, T=1, fh=5, fw=3, sparsity=0.0, seed=4),
+    # 8x16 patches: 128-token blocks (the window of the paper's own experiments), divisible and ragged frames
+    "bf16_8x16_T5": W.Workload("bf16_8x16_T5", B=1, H=2, d=128, T=5, fh=32, fw=48, ph=8, pw=16, sparsity=0.5, seed=5),
+    "bf16_8x16_ragged": W.Workload("bf16_8x16_ragged", B=1, H=1, d=128, T=3, fh=30, fw=52, ph=8, pw=16, sparsity=0.5,
+                                   seed=6),
 }
 
 
@@ -90,14 +94,14 @@ def test_permute_bit_exact(torch_mod, cases, name):
         assert np.array_equal(vt_to_rows(hvt[b, h], dims.g, w.d, dims.block), want)
         assert np.array_equal(hback[b, h], oa.restore(want, ref.inv))
     assert np.array_equal(hback, V)          # restore(reorder(X)) == X
-    if w.dtype == W.BF16 and dims.block == 64 and w.d % 32 == 0:
+    if w.dtype == W.BF16 and dims.block % 64 == 0 and w.d % 32 == 0:
         vo = empty((w.B, w.H, dims.g, dims.block * w.d), w.dtype)
         vo.fill_(7.0)
         da.da_permute(p, x, vo, da.DA_REORDER_VOP)
         torch.cuda.synchronize()
         hvo = to_host_storage(vo, w.dtype)
         for (b, h), ref in refs.items():
-            assert np.array_equal(vop_to_rows(hvo[b, h], dims.g, w.d), oa.permute(V[b, h], ref.perm))
+            assert np.array_equal(vop_to_rows(hvo[b, h], dims.g, w.d, dims.block), oa.permute(V[b, h], ref.perm))
 
 
 def test_permute_other_windows(torch_mod):
@@ -317,7 +321,7 @@ def test_sparse_attn_score_profiles(torch_mod, cases, profile):
     ref = refs[(0, 0)]
     g = ref.dims["g"]
     say(f"sparse_attn score profile {profile}")
-    blk = ref.inv // 64                                   # block of every token
+    blk = ref.inv // ref.dims["block"]                     # block of every token
     kf = oa.widen_f64(K[0, 0], w.dtype)
     qf = oa.widen_f64(Q[0, 0], w.dtype)
     if profile == "rising":

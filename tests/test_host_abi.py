@@ -76,8 +76,10 @@ def test_null_alignment_mode_and_support_checks():
     assert _status(da.da_select_blocks, p, None, FAKE, None, 0) == -1
     assert _status(da.da_select_blocks, p, FAKE, FAKE + 2, None, 0) == -5
     assert _status(da.da_sparse_attn, p, FAKE, FAKE, FAKE, None, FAKE, None, 0) == -1
-    # unsupported shapes for the attention kernels: window not 64 slots, head dim, dtype/d pair
-    for q in (da.problem(1, 1, 2, 16, 16, 128, ph=8, pw=16), da.problem(1, 1, 2, 16, 16, 96),
+    # unsupported shapes for the attention kernels: window of neither 64 nor 128 slots (bf16) or not 64 (f32),
+    # head dim, dtype/d pair
+    for q in (da.problem(1, 1, 2, 16, 16, 128, ph=4, pw=8), da.problem(1, 1, 2, 16, 16, 96),
+              da.problem(1, 1, 2, 16, 16, 64, ph=8, pw=16, dtype=da.DA_F32),
               da.problem(1, 1, 2, 16, 16, 64, dtype=da.DA_BF16), da.problem(1, 1, 2, 16, 16, 256, dtype=da.DA_F32)):
         assert _status(da.da_sparse_attn, q, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0) == -3
     # bf16 attention keeps per-workgroup block lists in LDS: more than ~7000 blocks with nothing dropped do not fit
