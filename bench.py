@@ -87,7 +87,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="720p_hunyuan", choices=list(W.CONFIGS))
+    ap.add_argument("--config", default="720p_hunyuan", choices=list(W.CONFIGS) + list(W.EXTRA_CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -95,7 +95,7 @@ def main():
               "by heads with no collectives); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
-    w = W.CONFIGS[args.config]
+    w = W.CONFIGS[args.config] if args.config in W.CONFIGS else W.EXTRA_CONFIGS[args.config]
     t0 = time.time()
     Q, K, V = W.make_qkv(w, threads=8)
     print(f"[bench] inputs for {w.name} generated in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)

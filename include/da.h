@@ -81,9 +81,10 @@ enum {
   DA_RESTORE = 2,      /* Xp [B,H,n_pad,d] -> X [B,H,N,d]; X[n] = Xp[pi^-1[n]] */
   DA_REORDER_VOP = 3   /* X [B,H,N,d] -> Xo [B,H,g,block*d]: the transposed block cut into the 16-byte operands of the
                           bf16 matrix instructions, each operand group of 64 stored contiguously (what da_sparse_attn
-                          wants for V with DA_BF16).  Only for DA_BF16, block == 64 and d a multiple of 32.  With
-                          nd = d/32, 16-byte unit ((t*nd + dt)*64 + hh*32 + r) of block i holds, for e = 0..7,
-                          X[pi[i*64 + 16t + 8hh + e]][32dt + r]   (t < 4, dt < nd, hh < 2, r < 32), zeros in pad
+                          wants for V with DA_BF16).  Only for DA_BF16, block a multiple of 64 and d a multiple of 32.
+                          The reordered sequence is cut into sub-blocks of 64 slots; with nd = d/32, 16-byte unit
+                          ((t*nd + dt)*64 + hh*32 + r) of sub-block b holds, for e = 0..7,
+                          X[pi[b*64 + 16t + 8hh + e]][32dt + r]   (t < 4, dt < nd, hh < 2, r < 32), zeros in pad
                           slots */
 };
 
@@ -138,18 +139,18 @@ int da_permute(const da_problem* p, const void* X, void* Y, int mode, void* stre
  * probability 0.  Op [B,H,n_pad,d] in the problem's dtype; rows of pad query slots are
  * written with unspecified finite values.  lse [B,H,n_pad] float (may be NULL) receives the
  * natural-log normaliser of each row.
- * Supported: block == 64 and (dtype, d) in {(DA_BF16, 128), (DA_F32, 64), (DA_F32, 128)};
- * anything else returns DA_ERR_UNSUPPORTED.  bf16 uses bf16 MFMA with float32 accumulation and
+ * Supported: DA_BF16 with d = 128 and block = 64 or 128 (8x8 or 8x16 patches, say); DA_F32 with
+ * d = 64 or 128 and block = 64; anything else returns DA_ERR_UNSUPPORTED.  bf16 uses bf16 MFMA with float32 accumulation and
  * softmax (and bf16 probabilities); f32 uses float32 arithmetic throughout.
  * The bf16 kernel leaves out, tile by tile (32 queries x 64 keys), keys whose probability is
  * negligible: a tile is dropped when each of its scores is so far below the best score its query
  * has met so far that everything dropped from a row adds up to less than 2^-14 of the row's largest
- * term (the cut is log2(64 k) + 14 powers of two).  The result differs from the full sum by less
+ * term (the cut is log2(block * k) + 14 powers of two).  The result differs from the full sum by less
  * than a bf16 rounding of the output; how much work is saved depends on how peaked the attention is
  * (nothing is dropped when all scores of a row are within that range of each other).
- * The bf16 kernel keeps the block lists of four query blocks in LDS, which bounds the problem:
- * roughly g/2 + 4*min(g, 4k) bytes must fit in 32 KB (g up to about 7000 with nothing dropped, far
- * more when k << g), and g < 2^22; larger problems return DA_ERR_UNSUPPORTED.  Its waits for tiles are
+ * The bf16 kernel keeps the block lists of four query blocks (two when block = 128) in LDS, which
+ * bounds the problem: roughly g/2 + 4*min(g, 4k) bytes must fit in 32 KB (g up to about 7000 with
+ * nothing dropped, far more when k << g), and g * block / 64 < 2^22; larger problems return DA_ERR_UNSUPPORTED.  Its waits for tiles are
  * bounded; should one ever run out (no valid input makes it), the rows concerned are written as NaN.
  */
 int da_sparse_attn(const da_problem* p, const void* Qp, const void* Kp, const void* Vt,

@@ -69,6 +69,12 @@ CONFIGS = {
     "long": Workload("long", B=1, H=24, d=128, T=65, fh=45, fw=80, sparsity=0.90, drift=True),
 }
 
+# Beyond the baseline file: the window and frame shape of the paper's own experiments (Section 4.1):
+# 8x16 patches, i.e. 128-token blocks, on a 48x80 latent grid that they divide.
+EXTRA_CONFIGS = {
+    "768p_8x16": Workload("768p_8x16", B=1, H=24, d=128, T=33, fh=48, fw=80, ph=8, pw=16, sparsity=0.90),
+}
+
 
 # ----------------------------------------------------------------------------
 # storage-format helpers (format conversion only)

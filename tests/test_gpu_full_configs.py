@@ -23,13 +23,16 @@ pytestmark = pytest.mark.gpu
 PLAN = [("480p", None, [0, 7, 23]),
         ("720p_hunyuan", None, [0, 11, 23]),
         ("720p_wan", [0, 13, 27, 39], [0, 39]),
-        ("long", [0, 9, 17, 23], [0, 23])]
+        ("long", [0, 9, 17, 23], [0, 23]),
+        # the paper's own window and frame shape: 8x16 patches (128-token blocks), 48x80 latents
+        ("768p_8x16", [0, 5, 11, 23], [0, 23])]
+
 
 
 @pytest.mark.parametrize("name,heads,check", PLAN, ids=[p[0] for p in PLAN])
 def test_full_config(name, heads, check):
     import torch
-    w = W.CONFIGS[name]
+    w = W.CONFIGS[name] if name in W.CONFIGS else W.EXTRA_CONFIGS[name]
     heads = list(range(w.H)) if heads is None else heads
     t0 = time.time()
     say(f"{name}: generating {len(heads)} heads, N={w.N}")
