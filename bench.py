@@ -165,6 +165,28 @@ def main():
     reorder_bytes = 3.0 * (dims.n + dims.n_pad) * w.d * esz * w.B * w.H
     restore_bytes = 1.0 * (dims.n + dims.n_pad) * w.d * esz * w.B * w.H
 
+    # ---- what this machine sustains: a pure matrix-instruction loop (~10 ms of it) and a plain copy
+    sink = torch.empty(1 << 20, dtype=torch.float32, device="cuda")
+    da.da_probe_mfma_bf16(2000, sink)                      # warm-up
+    torch.cuda.synchronize()
+    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    pe[0].record()
+    probe_flop = da.da_probe_mfma_bf16(6000, sink)
+    pe[1].record()
+    torch.cuda.synchronize()
+    mfma_measured = probe_flop / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e12
+    csrc, cdst = dQ.view(torch.uint8).flatten(), torch.empty(dQ.numel() * dQ.element_size(), dtype=torch.uint8, device="cuda")
+    da.da_probe_copy(csrc, cdst, csrc.numel())
+    torch.cuda.synchronize()
+    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    pe[0].record()
+    for _ in range(4):
+        da.da_probe_copy(csrc, cdst, csrc.numel())
+    pe[1].record()
+    torch.cuda.synchronize()
+    copy_measured = 4 * 2.0 * csrc.numel() / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9
+    del cdst, sink
+
     out = {
         "metric": METRIC,
         "value": eff_flop / (ms_step * 1e-3) / 1e12,
@@ -180,10 +202,13 @@ def main():
                      "frac": eff_flop / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                      "traffic": (sum(ATTN_TRAFFIC_BYTES[w.name]) if w.name in ATTN_TRAFFIC_BYTES else None),
                      "traffic_unit": "bytes per launch (read + written)",
-                     "launch_ms": attn_ms, "flop_per_launch": eff_flop},
+                     "launch_ms": attn_ms, "flop_per_launch": eff_flop,
+                     "measured_mfma_loop": mfma_measured,
+                     "frac_of_measured": eff_flop / (attn_ms * 1e-3) / 1e12 / mfma_measured},
         "stages_ms": stage_ms,
         "hbm_stages": {"reorder_qkv_GBs": reorder_bytes / (stage_ms["reorder_qkv"] * 1e-3) / 1e9,
-                       "restore_GBs": restore_bytes / (stage_ms["restore"] * 1e-3) / 1e9, "peak_GBs": PEAK_HBM_GBS},
+                       "restore_GBs": restore_bytes / (stage_ms["restore"] * 1e-3) / 1e9, "peak_GBs": PEAK_HBM_GBS,
+                       "measured_copy_GBs": copy_measured},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, Q, K, V)

@@ -23,6 +23,7 @@ DA_OK = 0
 
 EXPORTS = ["da_derive", "da_workspace_size", "da_build_perm", "da_draft_map", "da_select_blocks",
            "da_permute", "da_sparse_attn", "da_forward", "da_status_string"]
+PROBE_EXPORTS = ["da_probe_mfma_bf16", "da_probe_copy"]      # include/da_probe.h
 
 
 class da_problem(ctypes.Structure):
@@ -62,6 +63,10 @@ def lib() -> ctypes.CDLL:
         L.da_permute.argtypes = [P, V, V, ctypes.c_int, V]
         L.da_sparse_attn.argtypes = [P, V, V, V, V, V, V, V]
         L.da_forward.argtypes = [P, V, V, V, V, V, V, ctypes.c_size_t, V]
+        L.da_probe_mfma_bf16.argtypes = [ctypes.c_int, V, ctypes.POINTER(ctypes.c_double), V]
+        L.da_probe_mfma_bf16.restype = ctypes.c_int
+        L.da_probe_copy.argtypes = [V, V, ctypes.c_size_t, V]
+        L.da_probe_copy.restype = ctypes.c_int
         L.da_status_string.argtypes = [ctypes.c_int]
         L.da_status_string.restype = ctypes.c_char_p
         for name in EXPORTS[:-1]:
@@ -145,3 +150,14 @@ def da_forward(p, Q, K, V, O, ws, idx_out=None, stream=None):
     nbytes = ws.numel() * ws.element_size()
     _check(lib().da_forward(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(idx_out), _ptr(ws),
                             ctypes.c_size_t(nbytes), _stream(stream)), "da_forward")
+
+
+def da_probe_mfma_bf16(iters: int, sink, stream=None) -> float:
+    """Enqueue the matrix-instruction loop; returns the flop one launch performs."""
+    flop = ctypes.c_double(0.0)
+    _check(lib().da_probe_mfma_bf16(int(iters), _ptr(sink), ctypes.byref(flop), _stream(stream)), "da_probe_mfma_bf16")
+    return float(flop.value)
+
+
+def da_probe_copy(src, dst, nbytes: int, stream=None):
+    _check(lib().da_probe_copy(_ptr(src), _ptr(dst), ctypes.c_size_t(int(nbytes)), _stream(stream)), "da_probe_copy")

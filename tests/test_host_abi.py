@@ -19,10 +19,13 @@ FAKE = 0x10000  # a non-NULL, 16-byte aligned value that is never dereferenced o
 
 def test_every_declared_symbol_is_exported():
     header = open(os.path.join(ROOT, "include", "da.h")).read()
-    declared = set(re.findall(r"\b(da_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(da_[a-z0-9_]+)\s*\(", header))
     assert declared == set(da.EXPORTS)
+    probes = set(re.findall(r"\b(da_[a-z0-9_]+)\s*\(", open(os.path.join(ROOT, "include", "da_probe.h")).read()))
+    assert probes == set(da.PROBE_EXPORTS)
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["da.h", "da_probe.h"]
     L = da.lib()
-    for name in declared:
+    for name in declared | probes:
         assert getattr(L, name) is not None
 
 
