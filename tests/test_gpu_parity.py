@@ -21,6 +21,8 @@ SMALL = {
     "bf16_720p_T2": W.CONFIGS["720p_hunyuan"].with_(name="bf16_720p_T2", H=2, T=2, sparsity=0.9),
     "f32_ragged": W.Workload("f32_ragged", B=2, H=1, d=64, T=2, fh=20, fw=12, sparsity=0.4, dtype=W.F32, seed=3),
     "bf16_one_block": W.Workload("bf16_one_block", B=1, H=1, d=128, T=1, fh=5, fw=3, sparsity=0.0, seed=4),
+    # two batches, a frame count that leaves a workgroup with one live frame out of four
+    "bf16_B2_T5": W.Workload("bf16_B2_T5", B=2, H=2, d=128, T=5, fh=16, fw=24, sparsity=0.6, seed=7),
     # 8x16 patches: 128-token blocks (the window of the paper's own experiments), divisible and ragged frames
     "bf16_8x16_T5": W.Workload("bf16_8x16_T5", B=1, H=2, d=128, T=5, fh=32, fw=48, ph=8, pw=16, sparsity=0.5, seed=5),
     "bf16_8x16_ragged": W.Workload("bf16_8x16_ragged", B=1, H=1, d=128, T=3, fh=30, fw=52, ph=8, pw=16, sparsity=0.5,
@@ -398,3 +400,26 @@ def test_forward_end_to_end(torch_mod, cases, name):
     torch.cuda.synchronize()
     assert torch.equal(O.view(torch.int16 if w.dtype == W.BF16 else torch.int32),
                        O2.view(torch.int16 if w.dtype == W.BF16 else torch.int32))
+
+
+def test_forward_keep_one_block(torch_mod, cases):
+    """k = 1: every query block attends to the single best key block (argmax, lowest index on ties)."""
+    torch = torch_mod
+    w, Q, K, V, _ = cases["bf16_480p_T3"]
+    say("forward k=1")
+    w1 = w.with_(H=1)
+    p = da.problem(w1.B, 1, w1.T, w1.fh, w1.fw, w1.d, dtype=w1.dtype, keep_blocks=1)
+    dims = da.da_derive(p)
+    assert dims.k == 1
+    ref = HeadRef(w1, Q[0, 0], K[0, 0], V[0, 0], keep_blocks=1)
+    O = empty((1, 1, dims.n, w.d), w.dtype)
+    idx = torch.empty((1, 1, dims.g, 1), dtype=torch.int32, device="cuda")
+    ws = torch.empty(da.da_workspace_size(p), dtype=torch.uint8, device="cuda")
+    da.da_forward(p, to_dev(Q[:, :1], w.dtype), to_dev(K[:, :1], w.dtype), to_dev(V[:, :1], w.dtype), O, ws, idx)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy()[0, 0], ref.idx)
+    want = oa.restore(ref.attention(), ref.inv)
+    emax, emean = output_error(to_host_f64(O, w.dtype)[0, 0], want)
+    say(f"  k=1: max-abs {emax:.3e} mean-abs {emean:.3e}")
+    assert emax <= 2e-2 and emean <= 2e-3
+
