@@ -1,5 +1,6 @@
-// SparseAttn for bf16 storage, d = 128, 64-token blocks, on the CDNA4 matrix cores
-// (v_mfma_f32_32x32x16_bf16, float32 accumulation): the shared-ring kernel.
+// SparseAttn for bf16 storage, d = 128, blocks of 64 or 128 tokens, on the CDNA4 matrix cores
+// (v_mfma_f32_32x32x16_bf16, float32 accumulation): the shared-ring kernel.  (Described for
+// 64-token blocks; what changes for 128 is said at the kernel.)
 //
 // Why tiles are shared.  With 64 queries against a 64-key tile the arithmetic intensity is
 // 64 flop per byte of K/V, far below the machine balance, and a kernel in which every query
@@ -23,8 +24,9 @@
 // feeds K row sigma(l%32) (sigma swaps bits 2 and 3): then the scores a lane holds in
 // accumulator registers 8t..8t+7 belong to keys 16t + 8*(l/32) + 0..7, exactly the eight
 // contraction elements the P^T operand of the second product needs, so P goes from accumulator
-// to operand without leaving the lane.  V arrives block-transposed from the reorder step, so
-// K rows are read from LDS, and V^T operands from global memory, as plain 16-byte pieces.
+// to operand without leaving the lane.  V arrives from the reorder step transposed and cut into
+// these operands (one product step's 64 operands are one contiguous KB), so K rows are read from
+// LDS, and V^T operands from global memory, as plain 16-byte pieces.
 //
 // The ring.  Eight 16 KB slots, each one K tile.  Tiles travel HBM/L2 -> LDS by 16-byte
 // direct-to-LDS loads; the lane that writes LDS position p of row r fetches global chunk
@@ -43,9 +45,10 @@
 // its queries; when every score of the tile is so far below the best the query has seen that
 // all such keys of a row together weigh less than 2^-14 of its largest term, the tile cannot
 // change the result at the precision of the output and its exponentials and second product are
-// skipped.  With peaked attention that is the common case,
-// so V^T operands are fetched from global memory (L2) straight into registers, only by the waves
-// that need them, while the exponentials are being computed.
+// skipped.  With peaked attention that is the common case, so V^T operands are fetched from
+// global memory (L2) straight into registers, only by the waves that need them, while the
+// exponentials are being computed; a wave whose tiles keep mattering asks for them before the
+// first product instead.
 //
 // The running max only moves (and O is rescaled) when a row max exceeds it by more than 2^8 in
 // the exponent's units; until then probabilities are formed against the stale max, which is
