@@ -282,6 +282,23 @@ __device__ __forceinline__ bool compute_tile(const unsigned char* const (&kaddr)
   return true;
 }
 
+// How the frames that do not fill a group of `fg` are spread over workgroups.
+struct TailPlan {
+  int full_groups;   // groups of fg frames
+  int rem;           // frames left over (0: no tail workgroups)
+  int per_wg;        // positions per tail workgroup
+  int tail_wgs;      // tail workgroups per head
+};
+__host__ __device__ inline TailPlan tail_plan(const Geo& q, int fg) {
+  TailPlan p;
+  p.full_groups = q.T / fg;
+  p.rem = q.T - p.full_groups * fg;
+  p.per_wg = p.rem ? fg / p.rem : 1;
+  const int per_frame = q.gh * q.gw;
+  p.tail_wgs = p.rem ? (per_frame + p.per_wg - 1) / p.per_wg : 0;
+  return p;
+}
+
 // SUB = 64-token sub-blocks per block (1: 8x8 patches, 2: 128-token blocks such as 8x16 patches).  A block of
 // 128 is two K tiles and two V tiles in a row, and its queries are four waves' worth: the workgroup then takes two
 // query blocks (two consecutive frames) instead of four, and a key block enters the union walk as two entries.
@@ -301,29 +318,47 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   // 8 XCDs).
   constexpr int FG = 4 / SUB;                         // query blocks (frames) per workgroup
   constexpr int BLOCK = BS * SUB;                     // slots per block
+  // The frames that do not fill a group (T mod FG of them) are taken position by position into
+  // workgroups of their own, FG / (T mod FG) positions each: their lists have little in common, but
+  // a workgroup with one live query block out of four would cost as much as a full one.
   const int per_frame = q.gh * q.gw;
-  const int fgs = (q.T + FG - 1) / FG;
+  const TailPlan plan = tail_plan(q, FG);
+  const int fgs = plan.full_groups;
   const int pos_per_xcd = (per_frame + 7) >> 3;
-  const int wg_per_head = 8 * pos_per_xcd * fgs;
+  const int regular = 8 * pos_per_xcd * fgs;
+  const int wg_per_head = regular + plan.tail_wgs;
   const long long bh = blockIdx.x / wg_per_head;
   const int n = blockIdx.x - (int)(bh * wg_per_head);
-  const int xcd = n & 7, slot_id = n >> 3;
-  const int pos = xcd + 8 * (slot_id / fgs);
-  if (pos >= per_frame) return;                       // the whole workgroup leaves together
   // waves w and w+4 share a SIMD: give them different query blocks.  part = which 32 queries of the block.
   const int half = wave >> 2;
   const int qblk = SUB == 1 ? (wave + 2 * half) & 3 : half;
   const int part = SUB == 1 ? half : wave & 3;
-  const int f = FG * (slot_id % fgs) + qblk;
-  const bool live = f < q.T;                          // a wave past the last frame only helps with the ring
-  const long long qb = bh * q.g + (long long)min(f, q.T - 1) * per_frame + pos;
+  // query block w of this workgroup: (position, frame), or none
+  auto slot_pos = [&](int w) -> int {
+    if (n < regular) return (n & 7) + 8 * ((n >> 3) / fgs);
+    return w < plan.per_wg * plan.rem ? (n - regular) * plan.per_wg + w / plan.rem : per_frame;
+  };
+  auto slot_frame = [&](int w) -> int {
+    if (n < regular) return FG * ((n >> 3) % fgs) + w;
+    return fgs * FG + w % plan.rem;
+  };
+  // block number of query block w, -1 if the slot is empty
+  auto slot_block = [&](int w) -> int {
+    const int p = slot_pos(w), fr = slot_frame(w);
+    return p < per_frame && fr < q.T ? fr * per_frame + p : -1;
+  };
+  if (n < regular && slot_pos(0) >= per_frame) return;   // a regular workgroup past the last position: all of it leaves
+  const int my_block = slot_block(qblk);
+  const bool live = my_block >= 0;                    // a wave without a query block only helps with the ring
+  const int pos = live ? slot_pos(qblk) : 0;
+  const long long qb = bh * q.g + (live ? my_block : 0);
   const int k = q.k, g = q.g;
 
   // Q fragments (B operand): lane (query r, half-wave hh) holds d = 16t + 8hh .. +7.  Asked for
   // first, so that they arrive while the lists are being merged.
   // With `direct`, Qp and Op are Q and O in the original token order: the reordering of Q and the
   // restoring of O (Algorithms 1 and 2) are then this kernel's addressing, slot -> token.
-  const BlockPos qpos = block_pos(q, (int)(min(f, q.T - 1) * per_frame + pos));
+  const BlockPos qpos = block_pos(q, live ? my_block : 0);
   // row of slot s of my query block in Qp / Op, or -1 (pad slot of the original order)
   auto row_of = [&](int s) -> long long {
     if (!direct) return qb * BLOCK + s;
@@ -371,11 +406,14 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   // The workgroup's own blocks go first (when kept): a query's best scores tend to be
   // there, and the sooner the running maximum is near its final value, the more of the other
   // tiles turn out negligible.
-  const int own_lo = (FG * (slot_id % fgs)) * per_frame + pos;   // own blocks: own_lo + w * per_frame, w < FG
+  int own_j[FG];                                      // the workgroup's own blocks (-1: empty slot)
+#pragma unroll
+  for (int w = 0; w < FG; ++w) own_j[w] = slot_block(w);
   // membership of key block j in the workgroup's lists (0 for the own blocks unless asked for)
   auto membership = [&](int j, bool want_own) -> unsigned {
-    const int dj = j - own_lo;
-    const bool own = dj >= 0 && dj < FG * per_frame && dj % per_frame == 0;
+    bool own = false;
+#pragma unroll
+    for (int w = 0; w < FG; ++w) own = own || j == own_j[w];
     unsigned m4 = 0;
     if (j < g && own == want_own) {
 #pragma unroll
@@ -406,8 +444,10 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
     }
     if (lane == 0) wcount[wave] = cnt;
     if (wave == 0) {
-      const int j = own_lo + lane * per_frame;
-      const unsigned m4 = lane < FG ? membership(j, true) : 0u;
+      int j = -1;
+#pragma unroll
+      for (int w = 0; w < FG; ++w) j = lane == w ? own_j[w] : j;
+      const unsigned m4 = j >= 0 ? membership(j, true) : 0u;
       const bool two = m4 != 0u && second(j);
       const unsigned long long nz = __ballot(m4 != 0u), n2 = __ballot(two);
       if (m4) put_entries(lanes_before(nz) + lanes_before(n2), j, m4, two);
@@ -675,7 +715,8 @@ hipError_t launch_attn_bf16_ring(const Geo& q, const void* Qp, const void* Kp, c
                                  void* Op, float* lse, bool direct, hipStream_t s) {
   const int per_frame = q.gh * q.gw;
   const int sub = q.block / ring::BS, fg = 4 / sub;
-  unsigned grid = (unsigned)((long long)q.B * q.H * 8 * ((per_frame + 7) / 8) * ((q.T + fg - 1) / fg));
+  const ring::TailPlan plan = ring::tail_plan(q, fg);
+  unsigned grid = (unsigned)((long long)q.B * q.H * (8 * ((per_frame + 7) / 8) * plan.full_groups + plan.tail_wgs));
   const int balance = attn_bf16_ring_fits(q) == 2 ? 1 : 0;
   const float skip = log2f((float)q.k * (float)q.block) + ring::kDropLog2;
   if (sub == 1)
