@@ -349,16 +349,18 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   };
   if (n < regular && slot_pos(0) >= per_frame) return;   // a regular workgroup past the last position: all of it leaves
   const int my_block = slot_block(qblk);
-  const bool live = my_block >= 0;                    // a wave without a query block only helps with the ring
-  const int pos = live ? slot_pos(qblk) : 0;
-  const long long qb = bh * q.g + (live ? my_block : 0);
+  const bool has_block = my_block >= 0;
+  // a wave without a query block, or whose 32 slots of it are all pad slots, only helps with the ring
+  const bool live = has_block && 32 * part < block_valid(q, has_block ? my_block : 0);
+  const int pos = has_block ? slot_pos(qblk) : 0;
+  const long long qb = bh * q.g + (has_block ? my_block : 0);
   const int k = q.k, g = q.g;
 
   // Q fragments (B operand): lane (query r, half-wave hh) holds d = 16t + 8hh .. +7.  Asked for
   // first, so that they arrive while the lists are being merged.
   // With `direct`, Qp and Op are Q and O in the original token order: the reordering of Q and the
   // restoring of O (Algorithms 1 and 2) are then this kernel's addressing, slot -> token.
-  const BlockPos qpos = block_pos(q, live ? my_block : 0);
+  const BlockPos qpos = block_pos(q, has_block ? my_block : 0);
   // row of slot s of my query block in Qp / Op, or -1 (pad slot of the original order)
   auto row_of = [&](int s) -> long long {
     if (!direct) return qb * BLOCK + s;
@@ -664,7 +666,19 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   }
   publish();
   __syncthreads();                                    // everyone is done with the ring: reuse it to stage the output
-  if (!live) return;
+  if (!live) {
+    // 32 pad slots and nothing else: their rows of the reordered output are zeroed (in the original
+    // order they do not exist)
+    if (has_block && !direct) {
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int row = it * 4 + (lane >> 4), ch = lane & 15;
+        *(uint4*)(Op + (qb * BLOCK + 32 * part + row) * (D * 2) + ch * 16) = make_uint4(0u, 0u, 0u, 0u);
+      }
+      if (lse && lane < 32) lse[qb * BLOCK + 32 * part + lane] = 0.f;
+    }
+    return;
+  }
 
   // ---- epilogue: normalise, convert, stage through LDS, write rows of 256 B
   unsigned char* stage = smem + wave * (RING_BYTES / WAVES);
