@@ -328,18 +328,19 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   const int regular = 8 * pos_per_xcd * fgs;
   const int wg_per_head = regular + plan.tail_wgs;
   const long long bh = blockIdx.x / wg_per_head;
-  const int n = blockIdx.x - (int)(bh * wg_per_head);
+  // the tail workgroups (longer walks) come first within a head, the regular ones after them
+  const int n = blockIdx.x - (int)(bh * wg_per_head) - plan.tail_wgs;   // < 0: tail workgroup n + tail_wgs
   // waves w and w+4 share a SIMD: give them different query blocks.  part = which 32 queries of the block.
   const int half = wave >> 2;
   const int qblk = SUB == 1 ? (wave + 2 * half) & 3 : half;
   const int part = SUB == 1 ? half : wave & 3;
   // query block w of this workgroup: (position, frame), or none
   auto slot_pos = [&](int w) -> int {
-    if (n < regular) return (n & 7) + 8 * ((n >> 3) / fgs);
-    return w < plan.per_wg * plan.rem ? (n - regular) * plan.per_wg + w / plan.rem : per_frame;
+    if (n >= 0) return (n & 7) + 8 * ((n >> 3) / fgs);
+    return w < plan.per_wg * plan.rem ? (n + plan.tail_wgs) * plan.per_wg + w / plan.rem : per_frame;
   };
   auto slot_frame = [&](int w) -> int {
-    if (n < regular) return FG * ((n >> 3) % fgs) + w;
+    if (n >= 0) return FG * ((n >> 3) % fgs) + w;
     return fgs * FG + w % plan.rem;
   };
   // block number of query block w, -1 if the slot is empty
@@ -347,7 +348,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
     const int p = slot_pos(w), fr = slot_frame(w);
     return p < per_frame && fr < q.T ? fr * per_frame + p : -1;
   };
-  if (n < regular && slot_pos(0) >= per_frame) return;   // a regular workgroup past the last position: all of it leaves
+  if (n >= 0 && slot_pos(0) >= per_frame) return;     // a regular workgroup past the last position: all of it leaves
   const int my_block = slot_block(qblk);
   const bool has_block = my_block >= 0;
   // a wave without a query block, or whose 32 slots of it are all pad slots, only helps with the ring
