@@ -394,13 +394,21 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   int* next_load = ctrl + 16;
   int* count = ctrl + 17;                             // [2]
 
-  // ---- union of the workgroup's lists
+  // ---- union of the workgroup's lists (the first 256 entries of a list are asked for before the
+  // bitmaps are cleared, so that the two latencies overlap)
+  const bool lister = live && part == 0;              // the wave that brings in the list of its query block
+  const int32_t* list = idx + qb * k;
+  int pre[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) pre[i] = lister && lane + 64 * i < k ? list[lane + 64 * i] : -1;
   for (int i = threadIdx.x; i < 4 * bw; i += 512) bitmap[i] = 0u;
   if (threadIdx.x < 32) ctrl[threadIdx.x] = threadIdx.x < RING ? -1 : 0;
   __syncthreads();
-  if (live && part == 0) {
-    const int32_t* list = idx + qb * k;
-    for (int e = lane; e < k; e += 64) {
+  if (lister) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (pre[i] >= 0) atomicOr(&bitmap[qblk * bw + (pre[i] >> 5)], 1u << (pre[i] & 31));
+    for (int e = lane + 256; e < k; e += 64) {
       int j = list[e];
       atomicOr(&bitmap[qblk * bw + (j >> 5)], 1u << (j & 31));
     }
@@ -440,10 +448,31 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   const int c_lo = wave * cpw, c_hi = min(chunks, c_lo + cpw);
   {
     int cnt = 0;
-    for (int c = c_lo; c < c_hi; ++c) {
-      const int j = c * 64 + lane;
-      const bool in = membership(j, false) != 0u;
-      cnt += __popcll(__ballot(in)) + (SUB == 2 ? __popcll(__ballot(in && second(j))) : 0);
+    if (SUB == 1) {
+      // one entry per key block in any list: count the bits of the OR of the bitmaps, word by word
+      // (lane l takes word l of the wave's range), minus the own blocks among them
+      const int w_lo = 2 * c_lo, w_hi = min(2 * c_hi, bw);
+      for (int base = w_lo; base < w_hi; base += 64) {
+        const int word = base + lane;
+        unsigned v = 0u;
+        if (word < w_hi) {
+#pragma unroll
+          for (int w = 0; w < FG; ++w) v |= bitmap[w * bw + word];
+#pragma unroll
+          for (int w = 0; w < FG; ++w)
+            if (own_j[w] >= 0 && (own_j[w] >> 5) == word) v &= ~(1u << (own_j[w] & 31));
+        }
+        int pop = __popc(v);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) pop += __shfl_xor(pop, o);
+        cnt += pop;
+      }
+    } else {
+      for (int c = c_lo; c < c_hi; ++c) {
+        const int j = c * 64 + lane;
+        const bool in = membership(j, false) != 0u;
+        cnt += __popcll(__ballot(in)) + __popcll(__ballot(in && second(j)));
+      }
     }
     if (lane == 0) wcount[wave] = cnt;
     if (wave == 0) {
@@ -488,23 +517,24 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
     const int nR = nU - n_own;
     unsigned* upos = ulist + union_max;               // position of an entry inside its class
     int* ccount = (int*)(smem + LDS_TOTAL - 256);     // [16] entries per class
-    if (wave == 0) {
-      int cc = 0;                                     // lane m keeps the running count of class m
+    {
+      // wave w numbers the entries of classes w + 1 and w + 9
+      const unsigned ma = (unsigned)wave + 1u, mb = (unsigned)wave + 9u;   // mb = 16 for the last wave: no such class
+      int ca = 0, cb = 0;
       for (int base = 0; base < nR; base += 64) {
         const int i = base + lane;
         const unsigned m4 = i < nR ? rest[i] >> 28 : 0u;
-        int mypos = 0;
-#pragma unroll
-        for (int m = 1; m < 16; ++m) {
-          unsigned long long b = __ballot(m4 == (unsigned)m);
-          int before = __builtin_amdgcn_mbcnt_hi((unsigned)(b >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)b, 0));
-          int have = __builtin_amdgcn_readlane(cc, m);
-          if (m4 == (unsigned)m) mypos = have + before;
-          if (lane == m) cc += __popcll(b);
-        }
-        if (i < nR) upos[i] = (unsigned)mypos;
+        const unsigned long long ba = __ballot(m4 == ma), bb = __ballot(m4 == mb);
+        if (m4 == ma) upos[i] = (unsigned)(ca + lanes_before(ba));
+        if (m4 == mb) upos[i] = (unsigned)(cb + lanes_before(bb));
+        ca += __popcll(ba);
+        cb += __popcll(bb);
       }
-      if (lane < 16) ccount[lane] = lane == 0 ? 0 : cc;
+      if (lane == 0) {
+        ccount[ma] = ca;
+        if (mb < 16u) ccount[mb] = cb;
+        if (wave == 0) ccount[0] = 0;
+      }
     }
     __syncthreads();
     unsigned* sorted = upos + union_max;
