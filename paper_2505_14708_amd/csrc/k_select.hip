@@ -89,17 +89,27 @@ __global__ __launch_bounds__(64) void select_reg_kernel(const float* __restrict_
     key[i] = j < g ? order_key(in[j]) : 0u;           // a column past the end never counts: every trial value is > 0
   }
   unsigned thr = 0u;
+  bool cut = false;                                   // exactly k keys are >= thr: no tie to resolve, no bit left to find
   for (int bit = 31; bit >= 0; --bit) {
     const unsigned cand = thr | (1u << bit);
     int cnt = 0;
 #pragma unroll
     for (int i = 0; i < KPL; ++i) cnt += __popcll(__ballot(key[i] >= cand));
     if (cnt >= k) thr = cand;
+    if (cnt == k) {                                   // (the same in every lane)
+      cut = true;
+      break;
+    }
   }
-  // thr is now the k-th largest key
+  // thr is now the k-th largest key, or (cut) a value that exactly k keys reach
   int gt = 0;
+  if (cut) {
+    gt = k;                                           // all of them count as "greater": take key >= thr below
+    thr -= 1u;                                        // thr >= 1 here: a trial value is never 0
+  } else {
 #pragma unroll
-  for (int i = 0; i < KPL; ++i) gt += __popcll(__ballot(key[i] > thr));
+    for (int i = 0; i < KPL; ++i) gt += __popcll(__ballot(key[i] > thr));
+  }
   const int need_eq = k - gt;
   int written = 0, eq_seen = 0;
   int32_t* out = idx + row * k;
