@@ -12,6 +12,8 @@ What follows the paper where:
   pool_*               Definition 3.2, the two average-pooling equations
   draft_logits_*, draft_map   Definition 3.2, the draft attention map equation
   select_blocks        "Guided Sparsity via Draft Attention" paragraph (top entries kept)
+  select_blocks_global the threshold form of the mask, Section 3.2.2 "Error from Sparsity Mask"
+                       (t = the ceil(r g^2)-th largest region-level score of the whole map)
   lift_mask            the lifted mask equation  M^_uv = M_ij  (same paragraph)
   permute / restore    Section 3.3, Execution and Restoration paragraphs
   sparse_attention_*   the SparseAttn equation (same paragraph as the mask)
@@ -27,6 +29,13 @@ Readings taken where the paper is silent or loose (each is listed in the design 
   * the top entries are taken per query-block row (k per row), ranked on the float32
     draft logits (softmax is monotone per row, so the order is that of A_draft), ties
     to the lowest column index, lists ascending;
+  * the whole-map form (select_blocks_global) keeps exactly ceil(r g^2) entries of a head's
+    map: with distinct scores that is the paper's {S~_ij >= t}; scores equal to t are taken
+    in row-major order until the budget is used up (the per-row tie rule, extended), so the
+    size of the result does not depend on the data.  A row that the threshold leaves empty
+    keeps its single best column (lowest index on ties): the attention of its queries is
+    otherwise undefined.  The budget is g^2 - floor(sparsity*g^2 + 1e-6), or keep_blocks*g
+    when keep_blocks is given (the same total as k per row);
   * frames whose size the window does not divide get partial edge patches ("appropriate
     padding", Section 4.1): patches are anchored at (0,0) of each frame, a block holds
     its valid tokens in Algorithm 1's (u, v) raster order first and pad slots (index -1)
@@ -222,6 +231,44 @@ def select_blocks(scores, k):
     return idx, mask
 
 
+def global_budget(g, sparsity=0.0, keep_blocks=0):
+    """Entries of one head's g x g map kept by the whole-map selection: ceil(r g^2)."""
+    if keep_blocks and keep_blocks > 0:
+        total = int(keep_blocks) * g
+    else:
+        total = g * g - int(math.floor(sparsity * g * g + 1e-6))
+    return max(1, min(g * g, total))
+
+
+def select_blocks_global(scores, total):
+    """Whole-map threshold selection (Section 3.2.2): the ``total`` largest entries of the
+    map, equal scores in row-major order; rows left empty keep their best column.
+
+    Returns (row_ptr [g+1] int64, cols int64 (row by row, ascending inside a row),
+    mask [g, g] uint8).
+    """
+    scores = np.asarray(scores)
+    g_rows, g_cols = scores.shape
+    flat = scores.reshape(-1)
+    # stable sort of the negated map: descending score, equal scores by (row, column)
+    order = np.argsort(-flat, kind="stable")[:total]
+    mask = np.zeros(g_rows * g_cols, dtype=np.uint8)
+    mask[order] = 1
+    mask = mask.reshape(g_rows, g_cols)
+    for i in range(g_rows):
+        if not mask[i].any():
+            mask[i, int(np.argmax(scores[i]))] = 1          # argmax returns the first of equal maxima
+    counts = mask.sum(axis=1, dtype=np.int64)
+    row_ptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+    cols = np.nonzero(mask)[1].astype(np.int64)             # row-major: row by row, ascending columns
+    return row_ptr, cols, mask
+
+
+def lists_of(row_ptr, cols):
+    """The per-row lists of a (row_ptr, cols) pair, as sparse_attention_blocks takes them."""
+    return [cols[row_ptr[i]:row_ptr[i + 1]] for i in range(len(row_ptr) - 1)]
+
+
 def lift_mask(mask, perm, valid, block, n):
     """M^_uv = M_ij for u in R_i, v in R_j, over ORIGINAL token indices; [n, n] uint8."""
     region = np.empty(n, dtype=np.int64)
@@ -277,11 +324,13 @@ def sparse_attention_blocks(Qp64, Kp64, Vp64, idx, valid, block, rows=None, want
 # ----------------------------------------------------------------------------
 # the whole path for one head
 # ----------------------------------------------------------------------------
-def forward_head(Q, K, V, dtype, T, fh, fw, ph, pw, sparsity=0.0, keep_blocks=0, rows=None):
+def forward_head(Q, K, V, dtype, T, fh, fw, ph, pw, sparsity=0.0, keep_blocks=0, rows=None, whole_map=False):
     """pool -> draft logits (canonical float32) -> top-k -> reorder -> sparse attention
     -> restore, for one head.  Q, K, V are stored [N, d] arrays (float32 values or bf16
     bit patterns).  Returns a dict with every intermediate.  ``rows`` as above (the
-    restored output is then only meaningful for tokens of those query blocks)."""
+    restored output is then only meaningful for tokens of those query blocks).
+    ``whole_map``: the threshold selection over the whole map instead of k per row; the
+    result then carries row_ptr / cols, and idx is the list of per-row lists."""
     dims = derive_dims(T, fh, fw, ph, pw, sparsity, keep_blocks)
     block, n, k = dims["block"], dims["n"], dims["k"]
     perm, valid = reorder_index(T, fh, fw, ph, pw)
@@ -290,11 +339,16 @@ def forward_head(Q, K, V, dtype, T, fh, fw, ph, pw, sparsity=0.0, keep_blocks=0,
     qp32 = pool_canonical_f32(q32, perm, valid, block)
     kp32 = pool_canonical_f32(k32, perm, valid, block)
     L32 = draft_logits_canonical_f32(qp32, kp32)
-    idx, mask = select_blocks(L32, k)
+    row_ptr = cols = None
+    if whole_map:
+        row_ptr, cols, mask = select_blocks_global(L32, global_budget(dims["g"], sparsity, keep_blocks))
+        idx = lists_of(row_ptr, cols)
+    else:
+        idx, mask = select_blocks(L32, k)
     Qp = permute(widen_f64(Q, dtype), perm)
     Kp = permute(widen_f64(K, dtype), perm)
     Vp = permute(widen_f64(V, dtype), perm)
     Op = sparse_attention_blocks(Qp, Kp, Vp, idx, valid, block, rows=rows)
     O = restore(Op, inv)
     return dict(dims=dims, perm=perm, inv=inv, valid=valid, q_pool=qp32, k_pool=kp32,
-                logits=L32, idx=idx, mask=mask, Op=Op, O=O)
+                logits=L32, idx=idx, mask=mask, row_ptr=row_ptr, cols=cols, Op=Op, O=O)

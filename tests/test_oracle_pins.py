@@ -272,6 +272,116 @@ def test_select_order_equals_order_of_softmax_when_distinct():
     assert np.array_equal(oa.select_blocks(L, 7)[0], oa.select_blocks(A, 7)[0])
 
 
+# ---------------------------------------------------------------- whole-map selection (Section 3.2.2)
+def _brute_select_global(L, total):
+    g = len(L)
+    flat = [(-float(L[i][j]), i, j) for i in range(g) for j in range(len(L[i]))]
+    kept = sorted(flat)[:total]
+    rows = [[] for _ in range(g)]
+    for _, i, j in kept:
+        rows[i].append(j)
+    for i in range(g):
+        if not rows[i]:
+            best = max(float(v) for v in L[i])
+            rows[i] = [min(j for j in range(len(L[i])) if float(L[i][j]) == best)]
+        rows[i].sort()
+    return rows
+
+
+def test_global_budget_is_ceil_r_g2():
+    from fractions import Fraction
+    for g, s in ((8, "0.5"), (588, "0.75"), (1980, "0.9"), (1260, "0.75"), (3900, "0.9"), (990, "0.9"), (7, "0.55")):
+        exact = math.ceil((1 - Fraction(s)) * g * g)
+        assert oa.global_budget(g, float(s)) == exact
+    assert oa.global_budget(12, 0.5, keep_blocks=5) == 60             # the same total as 5 per row
+    assert oa.global_budget(12, 0.9999999) == 1                       # never empty
+    assert oa.global_budget(12, 0.0) == 144
+
+
+def test_global_select_brute_force_random_and_duplicates():
+    r = _rng(21)
+    for trial in range(8):
+        g = int(r.integers(2, 40))
+        total = int(r.integers(1, g * g + 1))
+        L = r.normal(size=(g, g)).astype(np.float32)
+        if trial % 2:
+            L = np.round(L * 2) / 2                                   # many exact duplicates, also at the threshold
+        row_ptr, cols, mask = oa.select_blocks_global(L, total)
+        want = _brute_select_global(L, total)
+        got = [list(x) for x in oa.lists_of(row_ptr, cols)]
+        assert got == want
+        forced = sum(1 for i in range(g) if len(want[i]) == 1 and
+                     (-float(L[i][want[i][0]]), i, want[i][0]) not in set(sorted(
+                         (-float(L[a][b]), a, b) for a in range(g) for b in range(g))[:total]))
+        assert row_ptr[-1] == total + forced == mask.sum()
+        for i in range(g):
+            assert np.array_equal(np.nonzero(mask[i])[0], want[i])
+
+
+def test_global_select_is_the_threshold_mask_when_scores_are_distinct():
+    r = _rng(22)
+    g, total = 30, 400
+    L = r.permutation(g * g).reshape(g, g).astype(np.float32)          # all distinct
+    row_ptr, cols, mask = oa.select_blocks_global(L, total)
+    t = np.sort(L.reshape(-1))[::-1][total - 1]                       # the ceil(r g^2)-th largest score
+    thr_mask = (L >= t)
+    empty = ~thr_mask.any(axis=1)
+    assert np.array_equal(mask[~empty], thr_mask[~empty].astype(np.uint8))
+    assert thr_mask.sum() == total
+    for i in np.nonzero(empty)[0]:                                    # rows under the threshold keep their best
+        assert mask[i].sum() == 1 and mask[i, np.argmax(L[i])] == 1
+
+
+def test_global_select_equals_per_row_when_rows_share_their_values():
+    # every row a rotation of the same distinct values: the k*g largest of the map are the k largest of each row
+    r = _rng(23)
+    g, k = 17, 5
+    base = r.permutation(g).astype(np.float32)
+    L = np.stack([np.roll(base, i) for i in range(g)])
+    row_ptr, cols, mask = oa.select_blocks_global(L, k * g)
+    idx, mask_rows = oa.select_blocks(L, k)
+    assert np.array_equal(mask, mask_rows)
+    assert np.array_equal(np.asarray(oa.lists_of(row_ptr, cols)), idx)
+    assert list(row_ptr) == [k * i for i in range(g + 1)]
+
+
+def test_global_select_special_cases():
+    # all equal: the budget is spent in row-major order, the rows after it keep column 0
+    L = np.zeros((4, 5), np.float32)
+    row_ptr, cols, mask = oa.select_blocks_global(L, 7)
+    assert [list(x) for x in oa.lists_of(row_ptr, cols)] == [[0, 1, 2, 3, 4], [0, 1], [0], [0]]
+    # a budget of one: the best entry of the map, and every other row its own best = one per row
+    r = _rng(24)
+    L = np.round(r.normal(size=(9, 9)) * 2).astype(np.float32)
+    row_ptr, cols, _ = oa.select_blocks_global(L, 1)
+    assert np.array_equal(cols, oa.select_blocks(L, 1)[0][:, 0])
+    # the whole map
+    row_ptr, cols, mask = oa.select_blocks_global(L, 81)
+    assert mask.all() and list(row_ptr) == list(range(0, 82, 9))
+    # worked by hand: scores 9 8 | 7 1 | 2 3 with a budget of 3 -> {9, 8, 7}; the last row keeps its 3
+    L = np.float32([[9, 8], [7, 1], [2, 3]])
+    row_ptr, cols, mask = oa.select_blocks_global(L, 3)
+    assert list(row_ptr) == [0, 2, 3, 4] and list(cols) == [0, 1, 0, 1]
+    # -0.0 ties with +0.0 (row-major order decides)
+    z = np.float32([[-0.0, -1.0], [0.0, 0.0]])
+    assert [list(x) for x in oa.lists_of(*oa.select_blocks_global(z, 2)[:2])] == [[0], [0]]
+
+
+def test_whole_map_forward_equals_masked_dense_attention():
+    # the lists of the whole-map selection, lifted to tokens, give the same output as the dense masked form
+    T, fh, fw, ph, pw, d = 2, 5, 6, 2, 4, 8
+    r = _rng(25)
+    n = T * fh * fw
+    Q, K, V = (r.normal(size=(n, d)).astype(np.float32) for _ in range(3))
+    res = oa.forward_head(Q, K, V, oa.F32, T, fh, fw, ph, pw, sparsity=0.6, whole_map=True)
+    g, block = res["dims"]["g"], res["dims"]["block"]
+    assert res["row_ptr"][-1] >= oa.global_budget(g, 0.6)
+    Mhat = oa.lift_mask(res["mask"], res["perm"], res["valid"], block, n)
+    dense = oa.sparse_attention_dense(Q.astype(np.float64), K.astype(np.float64), V.astype(np.float64), Mhat)
+    assert np.allclose(res["O"], dense, atol=1e-12)
+
+
+
 # ---------------------------------------------------------------- attention
 def _full_attention_loops(Q, K, V):
     n, d = Q.shape
