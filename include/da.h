@@ -7,6 +7,7 @@
  *   pool Q,K inside each latent frame      Definition 3.2 (average pooling equations)
  *   draft map  softmax(Q~ K~^T / sqrt(d))  Definition 3.2 (draft attention map equation)
  *   keep the top k key blocks per row      "Guided Sparsity via Draft Attention"
+ *     (or the top ceil(r g^2) of the map   Section 3.2.2, "Error from Sparsity Mask": the *_global and *_lists calls)
  *   reorder Q,K,V so a patch is a block    Algorithm 1, Section 3.3 "Execution"
  *   block-sparse attention                 SparseAttn equation, Section 3.1
  *   restore the order of O                 Algorithm 2, Section 3.3 "Restoration"
@@ -167,6 +168,51 @@ int da_sparse_attn(const da_problem* p, const void* Qp, const void* Kp, const vo
  */
 int da_forward(const da_problem* p, const void* Q, const void* K, const void* V, void* O,
                int32_t* idx_out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * The whole-map form of the guided sparsity (Section 3.2.2, "Error from Sparsity Mask"): the threshold t is the
+ * ceil(r g^2)-th largest score of a head's g x g map and M_ij = 1 where the score reaches t, so a row keeps as many
+ * key blocks as it has scores above the threshold.  Readings: r = 1 - sparsity and the budget is
+ * g^2 - floor(sparsity g^2 + 1e-6) entries (keep_blocks > 0: keep_blocks * g, the same total as that many per row);
+ * exactly that many are kept: scores equal to t are taken in row-major order until the budget is used up (-0 equals
+ * +0, NaN ranks below every number); a row that the threshold leaves empty keeps its best column (the lowest one
+ * on ties), since its queries' attention is otherwise undefined.
+ */
+typedef struct da_global_dims {
+  int64_t budget;     /* entries of one head's map kept by the threshold */
+  int64_t cap;        /* entries to allocate per (batch, head) for the lists: budget + g rounded up to a multiple of 4 */
+  size_t select_ws;   /* bytes of scratch da_select_blocks_global needs */
+  size_t forward_ws;  /* bytes of scratch da_forward_global needs */
+} da_global_dims;
+
+/* Host only, pure. */
+int da_global_sizes(const da_problem* p, da_global_dims* out /* host */);
+
+/*
+ * Whole-map selection on scores [B,H,g,g] (float).  row_ptr [B,H,g+1] int32 receives, per head, the offsets of the
+ * rows' lists (row_ptr[0] = 0, row_ptr[g] = entries kept, at most cap); cols [B,H,cap] int32 receives the kept
+ * columns, row after row, ascending inside a row (entries past row_ptr[g] are left as they were).  mask [B,H,g,g]
+ * uint8 may be NULL.  ws/ws_bytes: scratch of at least da_global_dims.select_ws bytes, 256-byte aligned.
+ */
+int da_select_blocks_global(const da_problem* p, const float* scores, int32_t* row_ptr, int32_t* cols, uint8_t* mask,
+                            void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * da_sparse_attn for lists of any length: query block i of head (b,h) attends the key blocks
+ * cols[(b*H+h)*cap + row_ptr[(b*H+h)*(g+1) + i] .. row_ptr[.. + i + 1]) (entries in [0,g), any order, no repeats;
+ * 0 <= row_ptr[..][i] <= row_ptr[..][i+1] <= cap; cap a multiple of 4).  A query block with an empty list gets zero
+ * rows.  Everything else as da_sparse_attn (its k is not used; the cut of the bf16 drop rule goes by each row's own
+ * number of keys); the bf16 kernel's LDS bound is that of k = g.
+ */
+int da_sparse_attn_lists(const da_problem* p, const void* Qp, const void* Kp, const void* Vt, const int32_t* row_ptr,
+                         const int32_t* cols, int64_t cap, void* Op, float* lse, void* stream);
+
+/*
+ * da_forward with the whole-map selection.  row_ptr_out [B,H,g+1] and cols_out [B,H,cap] (both or neither may be
+ * NULL) receive the kept blocks.  ws/ws_bytes: at least da_global_dims.forward_ws bytes, 256-byte aligned.
+ */
+int da_forward_global(const da_problem* p, const void* Q, const void* K, const void* V, void* O, int32_t* row_ptr_out,
+                      int32_t* cols_out, void* ws, size_t ws_bytes, void* stream);
 
 /* Static string for a da_status value (never NULL). */
 const char* da_status_string(int status);

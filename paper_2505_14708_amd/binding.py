@@ -22,7 +22,8 @@ def v_layout(dtype: int) -> int:
 DA_OK = 0
 
 EXPORTS = ["da_derive", "da_workspace_size", "da_build_perm", "da_draft_map", "da_select_blocks",
-           "da_permute", "da_sparse_attn", "da_forward", "da_status_string"]
+           "da_permute", "da_sparse_attn", "da_forward", "da_global_sizes", "da_select_blocks_global",
+           "da_sparse_attn_lists", "da_forward_global", "da_status_string"]
 PROBE_EXPORTS = ["da_probe_mfma_bf16", "da_probe_copy"]      # include/da_probe.h
 
 
@@ -35,6 +36,11 @@ class da_problem(ctypes.Structure):
 class da_dims(ctypes.Structure):
     _fields_ = [("gh", ctypes.c_int32), ("gw", ctypes.c_int32), ("g", ctypes.c_int32), ("block", ctypes.c_int32),
                 ("k", ctypes.c_int32), ("reserved", ctypes.c_int32), ("n", ctypes.c_int64), ("n_pad", ctypes.c_int64)]
+
+
+class da_global_dims(ctypes.Structure):
+    _fields_ = [("budget", ctypes.c_int64), ("cap", ctypes.c_int64), ("select_ws", ctypes.c_size_t),
+                ("forward_ws", ctypes.c_size_t)]
 
 
 class DaError(RuntimeError):
@@ -63,6 +69,10 @@ def lib() -> ctypes.CDLL:
         L.da_permute.argtypes = [P, V, V, ctypes.c_int, V]
         L.da_sparse_attn.argtypes = [P, V, V, V, V, V, V, V]
         L.da_forward.argtypes = [P, V, V, V, V, V, V, ctypes.c_size_t, V]
+        L.da_global_sizes.argtypes = [P, ctypes.POINTER(da_global_dims)]
+        L.da_select_blocks_global.argtypes = [P, V, V, V, V, V, ctypes.c_size_t, V]
+        L.da_sparse_attn_lists.argtypes = [P, V, V, V, V, V, ctypes.c_int64, V, V, V]
+        L.da_forward_global.argtypes = [P, V, V, V, V, V, V, V, ctypes.c_size_t, V]
         L.da_probe_mfma_bf16.argtypes = [ctypes.c_int, V, ctypes.POINTER(ctypes.c_double), V]
         L.da_probe_mfma_bf16.restype = ctypes.c_int
         L.da_probe_copy.argtypes = [V, V, ctypes.c_size_t, V]
@@ -150,6 +160,31 @@ def da_forward(p, Q, K, V, O, ws, idx_out=None, stream=None):
     nbytes = ws.numel() * ws.element_size()
     _check(lib().da_forward(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(idx_out), _ptr(ws),
                             ctypes.c_size_t(nbytes), _stream(stream)), "da_forward")
+
+
+def da_global_sizes(p: da_problem) -> da_global_dims:
+    out = da_global_dims()
+    _check(lib().da_global_sizes(ctypes.byref(p), ctypes.byref(out)), "da_global_sizes")
+    return out
+
+
+def da_select_blocks_global(p, scores, row_ptr, cols, ws, mask=None, stream=None):
+    nbytes = ws.numel() * ws.element_size()
+    _check(lib().da_select_blocks_global(ctypes.byref(p), _ptr(scores), _ptr(row_ptr), _ptr(cols), _ptr(mask), _ptr(ws),
+                                         ctypes.c_size_t(nbytes), _stream(stream)), "da_select_blocks_global")
+
+
+def da_sparse_attn_lists(p, Qp, Kp, Vt, row_ptr, cols, cap, Op, lse=None, stream=None):
+    _check(lib().da_sparse_attn_lists(ctypes.byref(p), _ptr(Qp), _ptr(Kp), _ptr(Vt), _ptr(row_ptr), _ptr(cols),
+                                      ctypes.c_int64(int(cap)), _ptr(Op), _ptr(lse), _stream(stream)),
+           "da_sparse_attn_lists")
+
+
+def da_forward_global(p, Q, K, V, O, ws, row_ptr_out=None, cols_out=None, stream=None):
+    nbytes = ws.numel() * ws.element_size()
+    _check(lib().da_forward_global(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(row_ptr_out),
+                                   _ptr(cols_out), _ptr(ws), ctypes.c_size_t(nbytes), _stream(stream)),
+           "da_forward_global")
 
 
 def da_probe_mfma_bf16(iters: int, sink, stream=None) -> float:

@@ -13,7 +13,7 @@ OBJ_DIR = os.path.join(HERE, "_build")
 LIB_DIR = os.path.join(HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libdraftattn.so")
 
-SOURCES = ["da_api.hip", "k_permute.hip", "k_pool.hip", "k_draft.hip", "k_select.hip", "k_attn_f32.hip",
+SOURCES = ["da_api.hip", "k_permute.hip", "k_pool.hip", "k_draft.hip", "k_select.hip", "k_select_global.hip", "k_attn_f32.hip",
            "k_attn_bf16_ring.hip", "k_probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -51,18 +51,33 @@ inline size_t elem_size(const Geo& q) { return q.dtype == DA_BF16 ? 2 : 4; }
 // row bytes must be a whole number of 16-byte chunks for the vector moves
 inline bool row_ok(const Geo& q) { return ((size_t)q.d * elem_size(q)) % 16 == 0; }
 
-inline bool attn_supported(const Geo& q) {
-  if (q.dtype == DA_BF16) return (q.block == 64 || q.block == 128) && q.d == 128 && attn_bf16_ring_fits(q) != 0;
+inline bool attn_supported(const Geo& q, bool any_length = false) {
+  if (q.dtype == DA_BF16)
+    return (q.block == 64 || q.block == 128) && q.d == 128 && attn_bf16_ring_fits(q, any_length) != 0;
   return q.block == 64 && (q.d == 64 || q.d == 128);
 }
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// Entries kept by the whole-map selection (Section 3.2.2: ceil(r g^2), here g^2 - floor(sparsity g^2 + 1e-6);
+// k per row given explicitly means the same total, k g) and the room to allocate per (batch, head): a row the
+// threshold leaves empty keeps one column, so up to g more.  Returns false when the offsets do not fit int32.
+bool global_budget(const da_problem* p, const Geo& q, long long* budget, long long* cap) {
+  const long long g2 = (long long)q.g * q.g;
+  long long b = p->keep_blocks > 0 ? (long long)q.k * q.g : g2 - (long long)floor(p->sparsity * (double)g2 + 1e-6);
+  if (b < 1) b = 1;
+  if (b > g2) b = g2;
+  *budget = b;
+  *cap = (b + q.g + 3) & ~3LL;                         // heads' lists stay 16-byte aligned
+  return *cap <= kMaxInt && (double)q.B * q.H * (double)*cap < 4.0e15;
+}
+
 struct Workspace {
-  size_t qp, kp, vt, op, q_pool, k_pool, logits, idx, total;
+  size_t qp, kp, vt, op, q_pool, k_pool, logits, idx, row_ptr, select, total;
 };
 
-Workspace plan_workspace(const Geo& q) {
+// lists_cap > 0: the whole-map selection (lists of any length, `lists_cap` entries per head) instead of k per row
+Workspace plan_workspace(const Geo& q, long long lists_cap = 0) {
   Workspace w;
   size_t bh = (size_t)q.B * q.H;
   size_t big = align_up(bh * (size_t)q.n_pad * q.d * elem_size(q));
@@ -77,7 +92,9 @@ Workspace plan_workspace(const Geo& q) {
   w.q_pool = off; off += pooled;
   w.k_pool = off; off += pooled;
   w.logits = off; off += align_up(bh * (size_t)q.g * q.g * sizeof(float));
-  w.idx = off; off += align_up(bh * (size_t)q.g * q.k * sizeof(int32_t));
+  w.idx = off; off += align_up(bh * (lists_cap > 0 ? (size_t)lists_cap : (size_t)q.g * q.k) * sizeof(int32_t));
+  w.row_ptr = off; off += lists_cap > 0 ? align_up(bh * ((size_t)q.g + 1) * sizeof(int32_t)) : 0;
+  w.select = off; off += lists_cap > 0 ? align_up(select_global_workspace(q)) : 0;
   w.total = off;
   return w;
 }
@@ -170,21 +187,26 @@ int da_sparse_attn(const da_problem* p, const void* Qp, const void* Kp, const vo
     return DA_ERR_ALIGN;
   if (!attn_supported(q)) return DA_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
-  if (q.dtype == DA_BF16) return hip_status(launch_attn_bf16_ring(q, Qp, Kp, Vt, idx, Op, lse, false, s));
-  return hip_status(launch_attn_f32(q, (const float*)Qp, (const float*)Kp, (const float*)Vt, idx, (float*)Op, lse, s));
+  if (q.dtype == DA_BF16) return hip_status(launch_attn_bf16_ring(q, Qp, Kp, Vt, idx, nullptr, 0, Op, lse, false, s));
+  return hip_status(
+      launch_attn_f32(q, (const float*)Qp, (const float*)Kp, (const float*)Vt, idx, nullptr, 0, (float*)Op, lse, s));
 }
 
-int da_forward(const da_problem* p, const void* Q, const void* K, const void* V, void* O, int32_t* idx_out,
-               void* ws, size_t ws_bytes, void* stream) {
+// da_forward and da_forward_global: the same launches but for the selection
+static int forward_impl(const da_problem* p, bool whole_map, const void* Q, const void* K, const void* V, void* O,
+                        int32_t* idx_out, int32_t* row_ptr_out, void* ws, size_t ws_bytes, void* stream) {
   Geo q;
   int st = check_problem(p, &q);
   if (st != DA_OK) return st;
   if (!Q || !K || !V || !O || !ws) return DA_ERR_NULL;
+  if (whole_map && (idx_out == nullptr) != (row_ptr_out == nullptr)) return DA_ERR_NULL;   // both or neither
   if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(idx_out) ||
-      ((uintptr_t)ws & 255u) != 0)
+      misaligned(row_ptr_out) || ((uintptr_t)ws & 255u) != 0)
     return DA_ERR_ALIGN;
-  if (!attn_supported(q) || !row_ok(q)) return DA_ERR_UNSUPPORTED;
-  Workspace w = plan_workspace(q);
+  if (!attn_supported(q, whole_map) || !row_ok(q)) return DA_ERR_UNSUPPORTED;
+  long long budget = 0, cap = 0;
+  if (whole_map && !global_budget(p, q, &budget, &cap)) return DA_ERR_DIM;
+  Workspace w = plan_workspace(q, cap);
   if (ws_bytes < w.total) return DA_ERR_WORKSPACE;
   char* base = (char*)ws;
   void* qp = base + w.qp;
@@ -195,31 +217,87 @@ int da_forward(const da_problem* p, const void* Q, const void* K, const void* V,
   float* k_pool = (float*)(base + w.k_pool);
   float* logits = (float*)(base + w.logits);
   int32_t* idx = idx_out ? idx_out : (int32_t*)(base + w.idx);
+  int32_t* row_ptr = !whole_map ? nullptr : row_ptr_out ? row_ptr_out : (int32_t*)(base + w.row_ptr);
   hipStream_t s = (hipStream_t)stream;
   hipError_t e;
+  const bool bf16 = q.dtype == DA_BF16;
   // Definition 3.2: pooled Q~, K~ and the draft logits (the ranking of a row of the draft
-  // map is the ranking of its logits, so the softmax itself is not needed here)
-  if (q.dtype == DA_BF16) {
-    // The pooling pass also writes the reordered K of Algorithm 1 (one read of K for both).  Q is
-    // not copied at all: the attention kernel reads its query rows from their original places and
-    // writes O's rows back to theirs, which is Algorithm 1 for Q and Algorithm 2 for O done by
-    // addressing (a row of 256 bytes is contiguous in either order).
-    if ((e = launch_pool_reorder(q, Q, K, q_pool, k_pool, nullptr, kp, s)) != hipSuccess) return DA_ERR_HIP;
-    if ((e = launch_draft_logits(q, q_pool, k_pool, logits, s)) != hipSuccess) return DA_ERR_HIP;
-    if ((e = launch_select(q, logits, idx, nullptr, s)) != hipSuccess) return DA_ERR_HIP;
-    if ((e = launch_permute(q, V, vt, DA_REORDER_VOP, s)) != hipSuccess) return DA_ERR_HIP;
-    return hip_status(launch_attn_bf16_ring(q, Q, kp, vt, idx, O, nullptr, true, s));
-  }
-  if ((e = launch_pool_reorder(q, Q, K, q_pool, k_pool, qp, kp, s)) != hipSuccess) return DA_ERR_HIP;
+  // map is the ranking of its logits, so the softmax itself is not needed here).
+  // The pooling pass also writes the reordered K of Algorithm 1 (one read of K for both).  With bf16, Q is
+  // not copied at all: the attention kernel reads its query rows from their original places and
+  // writes O's rows back to theirs, which is Algorithm 1 for Q and Algorithm 2 for O done by
+  // addressing (a row of 256 bytes is contiguous in either order).
+  if ((e = launch_pool_reorder(q, Q, K, q_pool, k_pool, bf16 ? nullptr : qp, kp, s)) != hipSuccess) return DA_ERR_HIP;
   if ((e = launch_draft_logits(q, q_pool, k_pool, logits, s)) != hipSuccess) return DA_ERR_HIP;
-  if ((e = launch_select(q, logits, idx, nullptr, s)) != hipSuccess) return DA_ERR_HIP;
-  // Algorithm 1: reorder V (block-transposed)
-  if ((e = launch_permute(q, V, vt, DA_REORDER_VT, s)) != hipSuccess) return DA_ERR_HIP;
+  // guided sparsity: k per row, or the threshold over the whole map (Section 3.2.2)
+  if (whole_map)
+    e = launch_select_global(q, budget, cap, logits, row_ptr, idx, nullptr, base + w.select, s);
+  else
+    e = launch_select(q, logits, idx, nullptr, s);
+  if (e != hipSuccess) return DA_ERR_HIP;
+  // Algorithm 1: reorder V (block-transposed; for bf16 as matrix operands)
+  if ((e = launch_permute(q, V, vt, bf16 ? DA_REORDER_VOP : DA_REORDER_VT, s)) != hipSuccess) return DA_ERR_HIP;
   // SparseAttn
-  e = launch_attn_f32(q, (const float*)qp, (const float*)kp, (const float*)vt, idx, (float*)op, nullptr, s);
+  if (bf16) return hip_status(launch_attn_bf16_ring(q, Q, kp, vt, idx, row_ptr, cap, O, nullptr, true, s));
+  e = launch_attn_f32(q, (const float*)qp, (const float*)kp, (const float*)vt, idx, row_ptr, cap, (float*)op, nullptr, s);
   if (e != hipSuccess) return DA_ERR_HIP;
   // Algorithm 2: restore
   return hip_status(launch_permute(q, op, O, DA_RESTORE, s));
+}
+
+int da_forward(const da_problem* p, const void* Q, const void* K, const void* V, void* O, int32_t* idx_out,
+               void* ws, size_t ws_bytes, void* stream) {
+  return forward_impl(p, false, Q, K, V, O, idx_out, nullptr, ws, ws_bytes, stream);
+}
+
+int da_global_sizes(const da_problem* p, da_global_dims* out) {
+  if (!out) return DA_ERR_NULL;
+  Geo q;
+  int st = check_problem(p, &q);
+  if (st != DA_OK) return st;
+  long long budget, cap;
+  if (!global_budget(p, q, &budget, &cap)) return DA_ERR_DIM;
+  out->budget = budget;
+  out->cap = cap;
+  out->select_ws = align_up(select_global_workspace(q));
+  out->forward_ws = plan_workspace(q, cap).total;
+  return DA_OK;
+}
+
+int da_select_blocks_global(const da_problem* p, const float* scores, int32_t* row_ptr, int32_t* cols, uint8_t* mask,
+                            void* ws, size_t ws_bytes, void* stream) {
+  Geo q;
+  int st = check_problem(p, &q);
+  if (st != DA_OK) return st;
+  if (!scores || !row_ptr || !cols || !ws) return DA_ERR_NULL;
+  if (misaligned(scores) || misaligned(row_ptr) || misaligned(cols) || misaligned(mask) || ((uintptr_t)ws & 255u) != 0)
+    return DA_ERR_ALIGN;
+  long long budget, cap;
+  if (!global_budget(p, q, &budget, &cap)) return DA_ERR_DIM;
+  if (ws_bytes < align_up(select_global_workspace(q))) return DA_ERR_WORKSPACE;
+  return hip_status(launch_select_global(q, budget, cap, scores, row_ptr, cols, mask, ws, (hipStream_t)stream));
+}
+
+int da_sparse_attn_lists(const da_problem* p, const void* Qp, const void* Kp, const void* Vt, const int32_t* row_ptr,
+                         const int32_t* cols, int64_t cap, void* Op, float* lse, void* stream) {
+  Geo q;
+  int st = check_problem(p, &q);
+  if (st != DA_OK) return st;
+  if (!Qp || !Kp || !Vt || !row_ptr || !cols || !Op) return DA_ERR_NULL;
+  if (cap < 1 || cap > kMaxInt || (cap & 3) != 0) return DA_ERR_DIM;
+  if (misaligned(Qp) || misaligned(Kp) || misaligned(Vt) || misaligned(row_ptr) || misaligned(cols) || misaligned(Op) ||
+      misaligned(lse))
+    return DA_ERR_ALIGN;
+  if (!attn_supported(q, true)) return DA_ERR_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  if (q.dtype == DA_BF16) return hip_status(launch_attn_bf16_ring(q, Qp, Kp, Vt, cols, row_ptr, cap, Op, lse, false, s));
+  return hip_status(launch_attn_f32(q, (const float*)Qp, (const float*)Kp, (const float*)Vt, cols, row_ptr, cap,
+                                    (float*)Op, lse, s));
+}
+
+int da_forward_global(const da_problem* p, const void* Q, const void* K, const void* V, void* O, int32_t* row_ptr_out,
+                      int32_t* cols_out, void* ws, size_t ws_bytes, void* stream) {
+  return forward_impl(p, true, Q, K, V, O, cols_out, row_ptr_out, ws, ws_bytes, stream);
 }
 
 const char* da_status_string(int status) {

@@ -63,12 +63,18 @@ hipError_t launch_pool_reorder(const Geo& q, const void* Q, const void* K, float
 hipError_t launch_draft_logits(const Geo& q, const float* q_pool, const float* k_pool, float* logits, hipStream_t s);
 hipError_t launch_row_softmax(const Geo& q, const float* logits, float* draft, hipStream_t s);
 hipError_t launch_select(const Geo& q, const float* scores, int32_t* idx, uint8_t* mask, hipStream_t s);
+// idx: k columns per row; or, with row_ptr [B,H,g+1], lists of any length, the lists of head bh one after the
+// other from idx + bh * cap on
 hipError_t launch_attn_f32(const Geo& q, const float* Qp, const float* Kp, const float* Vt, const int32_t* idx,
-                           float* Op, float* lse, hipStream_t s);
+                           const int32_t* row_ptr, long long cap, float* Op, float* lse, hipStream_t s);
+// whole-map threshold selection (k_select_global.hip)
+size_t select_global_workspace(const Geo& q);
+hipError_t launch_select_global(const Geo& q, long long budget, long long cap, const float* scores, int32_t* row_ptr,
+                                int32_t* cols, uint8_t* mask, void* ws, hipStream_t s);
 // bf16 block-sparse attention (k_attn_bf16_ring.hip)
-int attn_bf16_ring_fits(const Geo& q);
+int attn_bf16_ring_fits(const Geo& q, bool any_length = false);
 // direct: Qp and Op are Q and O in the original token order (lse stays in slot order)
 hipError_t launch_attn_bf16_ring(const Geo& q, const void* Qp, const void* Kp, const void* Vt, const int32_t* idx,
-                                 void* Op, float* lse, bool direct, hipStream_t s);
+                                 const int32_t* row_ptr, long long cap, void* Op, float* lse, bool direct, hipStream_t s);
 
 }  // namespace da

@@ -302,11 +302,13 @@ __host__ __device__ inline TailPlan tail_plan(const Geo& q, int fg) {
 // SUB = 64-token sub-blocks per block (1: 8x8 patches, 2: 128-token blocks such as 8x16 patches).  A block of
 // 128 is two K tiles and two V tiles in a row, and its queries are four waves' worth: the workgroup then takes two
 // query blocks (two consecutive frames) instead of four, and a key block enters the union walk as two entries.
-template <int SUB>
+// LISTS: the kept blocks come as lists of any length (row_ptr) instead of k per row.
+template <int SUB, bool LISTS>
 __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const unsigned char* __restrict__ Qp,
                                                                const unsigned char* __restrict__ Kp,
                                                                const unsigned char* __restrict__ Vt,
                                                                const int32_t* __restrict__ idx,
+                                                               const int32_t* __restrict__ row_ptr, long long cap,
                                                                unsigned char* __restrict__ Op, float* __restrict__ lse,
                                                                int balance, float skip, int direct) {
   __shared__ __attribute__((aligned(1024))) unsigned char smem[LDS_TOTAL];
@@ -355,7 +357,19 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   const bool live = has_block && 32 * part < block_valid(q, has_block ? my_block : 0);
   const int pos = has_block ? slot_pos(qblk) : 0;
   const long long qb = bh * q.g + (has_block ? my_block : 0);
-  const int k = q.k, g = q.g;
+  const int g = q.g;
+  // The list of my query block: k columns at idx + (row) * k, or, with row_ptr (lists of any length, one head's
+  // after the other in a stretch of `cap` entries), the columns between two offsets.
+  int k = q.k;
+  const int32_t* list = idx + qb * k;
+  if (LISTS) {
+    const int32_t* rp = row_ptr + bh * (g + 1) + (has_block ? my_block : 0);
+    const int begin = rp[0];
+    list = idx + bh * cap + begin;
+    k = rp[1] - begin;
+    // the cut of the drop rule goes by the number of keys in this row
+    skip = log2f((float)max(k, 1) * (float)BLOCK) + kDropLog2;
+  }
 
   // Q fragments (B operand): lane (query r, half-wave hh) holds d = 16t + 8hh .. +7.  Asked for
   // first, so that they arrive while the lists are being merged.
@@ -387,7 +401,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   unsigned* bitmap = (unsigned*)(smem + RING_BYTES);  // [FG][bw] one bitmap of kept key blocks per query block
   const int bw = (g + 31) >> 5;
   unsigned* ulist = bitmap + 4 * bw;                  // union entries: key sub-block | (valid slots - 1) << 22 | membership << 28
-  const int union_max = SUB * min(g, FG * k);
+  const int union_max = SUB * (LISTS ? g : min(g, FG * q.k));
   int* ctrl = (int*)(smem + LDS_TOTAL - 128);         // [32]: ready[8], prog[8], next_load, count, n_own
   int* ready = ctrl;                                  // [RING]
   int* prog = ctrl + 8;                               // [WAVES]
@@ -397,7 +411,6 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   // ---- union of the workgroup's lists (the first 256 entries of a list are asked for before the
   // bitmaps are cleared, so that the two latencies overlap)
   const bool lister = live && part == 0;              // the wave that brings in the list of its query block
-  const int32_t* list = idx + qb * k;
   int pre[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) pre[i] = lister && lane + 64 * i < k ? list[lane + 64 * i] : -1;
@@ -746,32 +759,32 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
 // LDS left beside the ring: four bitmaps of g bits, the union list (at most min(g, 4k) entries)
 // and, for the balanced walk, two more arrays of that length.
 // 0: the kernel cannot run this problem; 1: it can, walking in ascending order; 2: balanced walk.
-int attn_bf16_ring_fits(const Geo& q) {
+int attn_bf16_ring_fits(const Geo& q, bool any_length) {
   if (q.block != ring::BS && q.block != 2 * ring::BS) return 0;
   const int sub = q.block / ring::BS, fg = 4 / sub;
   if ((long long)q.g * sub >= (1 << 22)) return 0;
-  long long union_max = sub * ((long long)q.g < (long long)fg * q.k ? q.g : (long long)fg * q.k);
+  long long union_max = sub * ((long long)q.g < (long long)fg * q.k || any_length ? q.g : (long long)fg * q.k);
   long long base = 4LL * 4 * ((q.g + 31) / 32) + 4 * union_max + 512;
   if (base > ring::AUX_BYTES) return 0;
   return base + 8 * union_max <= ring::AUX_BYTES ? 2 : 1;
 }
 
 hipError_t launch_attn_bf16_ring(const Geo& q, const void* Qp, const void* Kp, const void* Vt, const int32_t* idx,
-                                 void* Op, float* lse, bool direct, hipStream_t s) {
+                                 const int32_t* row_ptr, long long cap, void* Op, float* lse, bool direct, hipStream_t s) {
   const int per_frame = q.gh * q.gw;
   const int sub = q.block / ring::BS, fg = 4 / sub;
   const ring::TailPlan plan = ring::tail_plan(q, fg);
   unsigned grid = (unsigned)((long long)q.B * q.H * (8 * ((per_frame + 7) / 8) * plan.full_groups + plan.tail_wgs));
-  const int balance = attn_bf16_ring_fits(q) == 2 ? 1 : 0;
+  const int balance = attn_bf16_ring_fits(q, row_ptr != nullptr) == 2 ? 1 : 0;
   const float skip = log2f((float)q.k * (float)q.block) + ring::kDropLog2;
-  if (sub == 1)
-    hipLaunchKernelGGL(ring::attn_bf16_ring_kernel<1>, dim3(grid), dim3(512), 0, s, q, (const unsigned char*)Qp,
-                       (const unsigned char*)Kp, (const unsigned char*)Vt, idx, (unsigned char*)Op, lse, balance, skip,
-                       direct ? 1 : 0);
-  else
-    hipLaunchKernelGGL(ring::attn_bf16_ring_kernel<2>, dim3(grid), dim3(512), 0, s, q, (const unsigned char*)Qp,
-                       (const unsigned char*)Kp, (const unsigned char*)Vt, idx, (unsigned char*)Op, lse, balance, skip,
-                       direct ? 1 : 0);
+  auto go = [&](auto kernel) {
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(512), 0, s, q, (const unsigned char*)Qp, (const unsigned char*)Kp,
+                       (const unsigned char*)Vt, idx, row_ptr, cap, (unsigned char*)Op, lse, balance, skip, direct ? 1 : 0);
+  };
+  if (sub == 1 && !row_ptr) go(ring::attn_bf16_ring_kernel<1, false>);
+  else if (sub == 1) go(ring::attn_bf16_ring_kernel<1, true>);
+  else if (!row_ptr) go(ring::attn_bf16_ring_kernel<2, false>);
+  else go(ring::attn_bf16_ring_kernel<2, true>);
   return hipGetLastError();
 }
 

@@ -14,6 +14,7 @@ namespace da {
 template <int D>
 __global__ __launch_bounds__(64) void attn_f32_kernel(Geo q, const float* __restrict__ Qp, const float* __restrict__ Kp,
                                                       const float* __restrict__ Vt, const int32_t* __restrict__ idx,
+                                                      const int32_t* __restrict__ row_ptr, long long cap,
                                                       float* __restrict__ Op, float* __restrict__ lse) {
   extern __shared__ __attribute__((aligned(16))) float smem_f[];
   float* ks = smem_f;            // [64][D]
@@ -32,8 +33,15 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(Geo q, const float* __rest
 #pragma unroll
   for (int c = 0; c < D; ++c) o[c] = 0.f;
   float m = -INFINITY, l = 0.f;
+  // k columns per row, or (row_ptr given) lists of any length, one after the other per head
   const int32_t* list = idx + qb * q.k;
-  for (int t = 0; t < q.k; ++t) {
+  int len = q.k;
+  if (row_ptr) {
+    const int32_t* rp = row_ptr + bh * (q.g + 1) + (qb - bh * q.g);
+    list = idx + bh * cap + rp[0];
+    len = rp[1] - rp[0];
+  }
+  for (int t = 0; t < len; ++t) {
     int j = list[t];
     int nv = block_valid(q, j);
     const float4* ksrc = (const float4*)(Kp + (bh * q.n_pad + (long long)j * 64) * D);
@@ -83,13 +91,13 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(Geo q, const float* __rest
 }
 
 hipError_t launch_attn_f32(const Geo& q, const float* Qp, const float* Kp, const float* Vt, const int32_t* idx,
-                           float* Op, float* lse, hipStream_t s) {
+                           const int32_t* row_ptr, long long cap, float* Op, float* lse, hipStream_t s) {
   unsigned blocks = (unsigned)((long long)q.B * q.H * q.g);
   size_t lds = (size_t)2 * 64 * q.d * sizeof(float);
   if (q.d == 64)
-    hipLaunchKernelGGL(attn_f32_kernel<64>, dim3(blocks), dim3(64), lds, s, q, Qp, Kp, Vt, idx, Op, lse);
+    hipLaunchKernelGGL(attn_f32_kernel<64>, dim3(blocks), dim3(64), lds, s, q, Qp, Kp, Vt, idx, row_ptr, cap, Op, lse);
   else
-    hipLaunchKernelGGL(attn_f32_kernel<128>, dim3(blocks), dim3(64), lds, s, q, Qp, Kp, Vt, idx, Op, lse);
+    hipLaunchKernelGGL(attn_f32_kernel<128>, dim3(blocks), dim3(64), lds, s, q, Qp, Kp, Vt, idx, row_ptr, cap, Op, lse);
   return hipGetLastError();
 }
 

@@ -32,6 +32,7 @@ def test_every_declared_symbol_is_exported():
 def test_struct_layout_matches_header():
     assert ctypes.sizeof(da.da_problem) == 48 and da.da_problem.sparsity.offset == 40
     assert ctypes.sizeof(da.da_dims) == 40 and da.da_dims.n.offset == 24
+    assert ctypes.sizeof(da.da_global_dims) == 32 and da.da_global_dims.select_ws.offset == 16
 
 
 def test_derive_matches_oracle_on_all_configs():
@@ -106,6 +107,37 @@ def test_forward_workspace_checks():
     # the workspace of the headline configuration is a few GB, far below one GPU's HBM
     big = da.da_workspace_size(da.problem_of(W.CONFIGS["720p_hunyuan"]))
     assert 1.5e9 < big < 6.0e9
+
+
+def test_global_sizes_match_oracle_and_checks():
+    for w in list(W.CONFIGS.values()) + list(W.EXTRA_CONFIGS.values()):
+        p = da.problem_of(w)
+        g = da.da_derive(p).g
+        sz = da.da_global_sizes(p)
+        assert sz.budget == oa.global_budget(g, w.sparsity), w.name
+        assert sz.budget + g <= sz.cap < sz.budget + g + 4 and sz.cap % 4 == 0
+        assert sz.forward_ws > sz.select_ws > 0
+    p = da.problem(1, 1, 12, 8, 8, 128, keep_blocks=5)
+    assert da.da_global_sizes(p).budget == oa.global_budget(12, keep_blocks=5) == 60
+    assert _status(da.da_global_sizes, da.problem(1, 1, 1, 8, 8, 128, sparsity=1.0)) == -2
+    # offsets of a head's lists are int32
+    assert _status(da.da_global_sizes, da.problem(1, 1, 60000, 8, 8, 128, sparsity=0.1)) == -2
+    p = da.problem_of(W.CONFIGS["480p"])
+    sz = da.da_global_sizes(p)
+    L = da.lib()
+    V = ctypes.c_void_p
+    assert L.da_select_blocks_global(ctypes.byref(p), V(FAKE), V(FAKE), V(FAKE), None, V(FAKE),
+                                     ctypes.c_size_t(sz.select_ws - 1), None) == -4
+    assert L.da_select_blocks_global(ctypes.byref(p), V(FAKE), None, V(FAKE), None, V(FAKE),
+                                     ctypes.c_size_t(sz.select_ws), None) == -1
+    assert L.da_select_blocks_global(ctypes.byref(p), V(FAKE), V(FAKE), V(FAKE), None, V(FAKE + 16),
+                                     ctypes.c_size_t(sz.select_ws), None) == -5
+    assert _status(da.da_sparse_attn_lists, p, FAKE, FAKE, FAKE, None, FAKE, sz.cap, FAKE, None, 0) == -1
+    assert _status(da.da_sparse_attn_lists, p, FAKE, FAKE, FAKE, FAKE, FAKE, 0, FAKE, None, 0) == -2
+    assert _status(da.da_sparse_attn_lists, p, FAKE, FAKE, FAKE, FAKE, FAKE, 6, FAKE, None, 0) == -2   # not a multiple of 4
+    args = [ctypes.byref(p)] + [V(FAKE)] * 4
+    assert L.da_forward_global(*args, None, None, V(FAKE), ctypes.c_size_t(sz.forward_ws - 1), None) == -4
+    assert L.da_forward_global(*args, V(FAKE), None, V(FAKE), ctypes.c_size_t(sz.forward_ws), None) == -1   # one of the two
 
 
 def test_status_strings():
