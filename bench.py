@@ -40,7 +40,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 ATTN_TRAFFIC_BYTES = {"720p_hunyuan": (57.84e9, 0.754e9)}
 
 
-def cpu_baseline(w, Q, K, V, budget_s=20.0):
+def cpu_baseline(w, Q, K, V, budget_s=20.0, whole_map=False):
     """Time the oracle (as it stands) on head 0: pooling, draft logits, selection and the
     reordering in full, the attention on as many evenly spaced query blocks as fit the
     budget; extrapolate to one layer."""
@@ -57,7 +57,11 @@ def cpu_baseline(w, Q, K, V, budget_s=20.0):
     inv = oa.restore_index(perm, dims["n"])
     qp = oa.pool_canonical_f32(oa.widen_f32(q, w.dtype), perm, valid, dims["block"])
     kp = oa.pool_canonical_f32(oa.widen_f32(k, w.dtype), perm, valid, dims["block"])
-    idx, _ = oa.select_blocks(oa.draft_logits_canonical_f32(qp, kp), dims["k"])
+    L = oa.draft_logits_canonical_f32(qp, kp)
+    if whole_map:
+        idx = oa.lists_of(*oa.select_blocks_global(L, oa.global_budget(dims["g"], w.sparsity))[:2])
+    else:
+        idx, _ = oa.select_blocks(L, dims["k"])
     Qp, Kp, Vp = (oa.permute(oa.widen_f64(x, w.dtype), perm) for x in (q, k, v))
     t_fixed = time.perf_counter() - t0
     g = dims["g"]
@@ -88,6 +92,9 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", default="720p_hunyuan", choices=list(W.CONFIGS) + list(W.EXTRA_CONFIGS))
+    ap.add_argument("--selection", default="rows", choices=["rows", "whole_map"],
+                    help="rows: k key blocks per query block (the headline); whole_map: the threshold over a head's "
+                         "whole map (Section 3.2.2), lists of any length")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -115,18 +122,29 @@ def main():
     dims = da.da_derive(p)
     dQ, dK, dV = dev(Q), dev(K), dev(V)
     O = torch.empty((w.B, w.H, dims.n, w.d), dtype=tdt, device="cuda")
-    ws = torch.empty(da.da_workspace_size(p), dtype=torch.uint8, device="cuda")
+    whole_map = args.selection == "whole_map"
+    gsz = da.da_global_sizes(p) if whole_map else None
+    ws = torch.empty(gsz.forward_ws if whole_map else da.da_workspace_size(p), dtype=torch.uint8, device="cuda")
     g, k = dims.g, dims.k
-    eff_flop = 4.0 * w.N * w.N * w.d * w.B * w.H * k / g
+    # kept fraction of the map: k/g per row, or the budget of the whole map over g^2 (rows the threshold
+    # leaves empty keep one block more each; not counted)
+    density = gsz.budget / (g * g) if whole_map else k / g
+    eff_flop = 4.0 * w.N * w.N * w.d * w.B * w.H * density
+
+    def step():
+        if whole_map:
+            da.da_forward_global(p, dQ, dK, dV, O, ws)
+        else:
+            da.da_forward(p, dQ, dK, dV, O, ws)
 
     # ---- the timed region: K steps of the whole path
     for _ in range(args.warmup):
-        da.da_forward(p, dQ, dK, dV, O, ws)
+        step()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(args.steps):
-        da.da_forward(p, dQ, dK, dV, O, ws)
+        step()
     e1.record()
     torch.cuda.synchronize()
     ms_step = e0.elapsed_time(e1) / args.steps
@@ -139,13 +157,21 @@ def main():
     q_pool = torch.empty((w.B, w.H, g, w.d), dtype=torch.float32, device="cuda")
     k_pool = torch.empty_like(q_pool)
     logits = torch.empty((w.B, w.H, g, g), dtype=torch.float32, device="cuda")
-    idx = torch.empty((w.B, w.H, g, k), dtype=torch.int32, device="cuda")
+    idx = torch.empty((w.B, w.H, gsz.cap if whole_map else g * k), dtype=torch.int32, device="cuda")
+    row_ptr = torch.empty((w.B, w.H, g + 1), dtype=torch.int32, device="cuda")
+    sel_ws = torch.empty(gsz.select_ws if whole_map else 256, dtype=torch.uint8, device="cuda")
+    if whole_map:
+        select = lambda: da.da_select_blocks_global(p, logits, row_ptr, idx, sel_ws)
+        attend = lambda: da.da_sparse_attn_lists(p, Qp, Kp, Vt, row_ptr, idx, gsz.cap, Op, None)
+    else:
+        select = lambda: da.da_select_blocks(p, logits, idx, None)
+        attend = lambda: da.da_sparse_attn(p, Qp, Kp, Vt, idx, Op, None)
     stages = [
         ("pool+draft_logits", lambda: da.da_draft_map(p, dQ, dK, q_pool, k_pool, logits, None)),
-        ("select", lambda: da.da_select_blocks(p, logits, idx, None)),
+        ("select", select),
         ("reorder_qkv", lambda: (da.da_permute(p, dQ, Qp, da.DA_REORDER_ROWS), da.da_permute(p, dK, Kp, da.DA_REORDER_ROWS),
                                  da.da_permute(p, dV, Vt, da.v_layout(p.dtype)))),
-        ("sparse_attn", lambda: da.da_sparse_attn(p, Qp, Kp, Vt, idx, Op, None)),
+        ("sparse_attn", attend),
         ("restore", lambda: da.da_permute(p, Op, O, da.DA_RESTORE)),
     ]
     acc = {name: 0.0 for name, _ in stages}
@@ -196,11 +222,13 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if w.dtype == W.F32 else "bf16", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "d": w.d, "T": w.T, "frame": [w.fh, w.fw], "N": w.N,
-                   "pool": [w.ph, w.pw], "sparsity": w.sparsity, "g": g, "k": k, "n_pad": int(dims.n_pad)},
+                   "pool": [w.ph, w.pw], "sparsity": w.sparsity, "g": g, "k": k, "n_pad": int(dims.n_pad),
+                   "selection": args.selection},
         "roofline": {"kernel": "da::ring::attn_bf16_ring_kernel (da_sparse_attn)", "bound": "mfma",
                      "achieved": eff_flop / (attn_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": eff_flop / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-                     "traffic": (sum(ATTN_TRAFFIC_BYTES[w.name]) if w.name in ATTN_TRAFFIC_BYTES else None),
+                     "traffic": (sum(ATTN_TRAFFIC_BYTES[w.name]) if w.name in ATTN_TRAFFIC_BYTES and not whole_map
+                                 else None),
                      "traffic_unit": "bytes per launch (read + written)",
                      "launch_ms": attn_ms, "flop_per_launch": eff_flop,
                      "measured_mfma_loop": mfma_measured,
@@ -210,8 +238,13 @@ def main():
                        "restore_GBs": restore_bytes / (stage_ms["restore"] * 1e-3) / 1e9, "peak_GBs": PEAK_HBM_GBS,
                        "measured_copy_GBs": copy_measured},
     }
+    if whole_map:
+        torch.cuda.synchronize()
+        lens = (row_ptr[:, :, 1:] - row_ptr[:, :, :-1]).flatten().cpu().numpy()
+        out["config"]["whole_map"] = {"budget_per_head": int(gsz.budget), "list_min": int(lens.min()),
+                                      "list_mean": float(lens.mean()), "list_max": int(lens.max())}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, Q, K, V)
+        out["cpu_baseline"] = cpu_baseline(w, Q, K, V, whole_map=whole_map)
     print(json.dumps(out), flush=True)
 
 

@@ -74,6 +74,56 @@ def test_full_config(name, heads, check):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("name,heads,check", [("720p_hunyuan", [0, 7, 16, 23], [0, 23]), ("768p_8x16", [3, 20], [20])],
+                         ids=["720p_hunyuan", "768p_8x16"])
+def test_full_config_whole_map(name, heads, check):
+    """The same with the whole-map selection (Section 3.2.2): one threshold per head, lists of any length."""
+    import torch
+    w = W.CONFIGS[name] if name in W.CONFIGS else W.EXTRA_CONFIGS[name]
+    say(f"{name} whole map: generating {len(heads)} heads")
+    Q, K, V = W.make_qkv(w, heads=heads, threads=8)
+    wg = w.with_(H=len(heads))
+    p = da.problem_of(wg)
+    dims = da.da_derive(p)
+    sz = da.da_global_sizes(p)
+    ws = torch.empty(sz.forward_ws, dtype=torch.uint8, device="cuda")
+    O = empty((1, len(heads), dims.n, w.d), w.dtype)
+    row_ptr = torch.empty((1, len(heads), dims.g + 1), dtype=torch.int32, device="cuda")
+    cols = torch.empty((1, len(heads), sz.cap), dtype=torch.int32, device="cuda")
+    dQ, dK, dV = (to_dev(x, w.dtype) for x in (Q, K, V))
+    da.da_forward_global(p, dQ, dK, dV, O, ws, row_ptr, cols)
+    torch.cuda.synchronize()
+    hrp, hcols = row_ptr.cpu().numpy(), cols.cpu().numpy()
+    say(f"{name} whole map: GPU done; g={dims.g} budget={sz.budget}")
+    # structure of every head's lists: offsets ascend, every row holds something, the budget is met
+    lens = np.diff(hrp, axis=-1)
+    assert (hrp[..., 0] == 0).all() and (lens >= 1).all() and (lens <= dims.g).all()
+    assert (hrp[..., -1] >= sz.budget).all() and (hrp[..., -1] <= sz.cap).all()
+    tol_max, tol_mean = TOL[w.dtype]
+    for h in check:
+        i = heads.index(h)
+        ref = HeadRef(w, Q[0, i], K[0, i], V[0, i])
+        r, c, _ = oa.select_blocks_global(ref.logits, sz.budget)
+        same = np.array_equal(hrp[0, i], r) and np.array_equal(hcols[0, i][:r[-1]], c)
+        say(f"{name} head {h}: lists {'match' if same else 'DIFFER'}; {lens[0, i].min()}..{lens[0, i].max()} blocks a row, "
+            f"{int((np.diff(r) == 1).sum())} rows of one")
+        assert same
+        lists = oa.lists_of(r, c)
+        rows = sorted(set(stratified_rows(ref, per_class=2, seed=h)) |
+                      {int(np.argmax(np.diff(r))), int(np.argmin(np.diff(r)))})      # the longest and a shortest list too
+        want = ref.attention(rows=rows, idx=lists)
+        got = to_host_f64(O[0, i], w.dtype)
+        worst = (0.0, 0.0)
+        for q in rows:
+            slots = np.arange(q * dims.block, q * dims.block + ref.valid[q])
+            emax, emean = output_error(got[ref.perm[slots]], want[slots])
+            worst = (max(worst[0], emax), max(worst[1], emean))
+        say(f"{name} head {h}: {len(rows)} sampled query blocks, worst max-abs {worst[0]:.3e} mean-abs {worst[1]:.3e}")
+        assert worst[0] <= tol_max and worst[1] <= tol_mean
+    del ws, O, dQ, dK, dV
+    torch.cuda.empty_cache()
+
+
 def test_many_blocks_ascending_walk():
     """A problem whose union lists are too long for the balanced walk's extra arrays (the kernel
     then walks in ascending order): 3000 one-patch frames, 800 key blocks kept per query block."""
