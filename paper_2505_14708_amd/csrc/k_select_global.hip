@@ -17,6 +17,7 @@ constexpr int kBins = 2048;
 constexpr int kHistThreads = 256;
 constexpr int kKeysPerThread = 16;                    // keys a thread of the histogram pass takes
 constexpr int kChunk = kHistThreads * kKeysPerThread;
+constexpr int kChunksPerGroup = 8;                    // chunks a workgroup takes before it adds its counts to the head's
 
 __device__ inline unsigned gkey(float x) {
   unsigned u = __float_as_uint(x);
@@ -49,39 +50,42 @@ __global__ void zero_words_kernel(unsigned* p, long long n) {
 
 // hist[bh][pass][bin] += number of keys of head bh whose higher digits equal the state's prefix and whose
 // digit of this pass is `bin`.  One workgroup takes kChunk consecutive scores of one head.
+template <int PASS>
 __global__ __launch_bounds__(kHistThreads) void hist_kernel(const float* __restrict__ scores, unsigned* __restrict__ hist,
-                                                           const SelState* __restrict__ state, long long g2, int pass) {
+                                                           const SelState* __restrict__ state, long long g2) {
+  constexpr int pass = PASS;
   __shared__ unsigned lh[kBins];
   const long long bh = blockIdx.y;
   for (int i = threadIdx.x; i < kBins; i += kHistThreads) lh[i] = 0u;
   const unsigned want = pass == 0 ? 0u : above_of(state[bh].prefix, pass);
   __syncthreads();
   const float* in = scores + bh * g2;
-  const long long base = (long long)blockIdx.x * kChunk;
-  float x[kKeysPerThread];
+  for (int c = 0; c < kChunksPerGroup; ++c) {
+    const long long base = ((long long)blockIdx.x * kChunksPerGroup + c) * kChunk;
+    if (base >= g2) break;
+    float x[kKeysPerThread];
 #pragma unroll
-  for (int i = 0; i < kKeysPerThread; ++i) {
-    const long long e = base + i * kHistThreads + threadIdx.x;
-    x[i] = e < g2 ? in[e] : 0.f;
-  }
-#pragma unroll
-  for (int i = 0; i < kKeysPerThread; ++i) {
-    const long long e = base + i * kHistThreads + threadIdx.x;
-    const unsigned key = gkey(x[i]);
-    bool mine = e < g2 && above_of(key, pass) == want;
-    const unsigned dg = digit_of(key, pass);
-    // The leading digit of scores of one map takes few values: lanes with the same digit add up among
-    // themselves first (a few rounds), what is left goes one by one.
-    unsigned long long todo = __ballot(mine);
-    for (int round = 0; round < 4 && todo != 0ull; ++round) {
-      const int leader = __builtin_ctzll(todo);
-      const unsigned d0 = (unsigned)__shfl((int)dg, leader);
-      const unsigned long long same = __ballot(mine && dg == d0);
-      if ((int)(threadIdx.x & 63) == leader) atomicAdd(&lh[d0], (unsigned)__popcll(same));
-      if (dg == d0) mine = false;
-      todo &= ~same;
+    for (int i = 0; i < kKeysPerThread; ++i) {
+      const long long e = base + i * kHistThreads + threadIdx.x;
+      x[i] = e < g2 ? in[e] : 0.f;
     }
-    if (mine) atomicAdd(&lh[dg], 1u);
+#pragma unroll
+    for (int i = 0; i < kKeysPerThread; ++i) {
+      const long long e = base + i * kHistThreads + threadIdx.x;
+      const unsigned key = gkey(x[i]);
+      bool mine = e < g2 && above_of(key, pass) == want;
+      const unsigned dg = digit_of(key, pass);
+      // When every lane of the wave holds the same digit (a constant map, say) one lane adds for all: the
+      // same-address adds of 64 lanes would go one by one.  Otherwise the digits of one map fall into a few
+      // dozen bins at most, and the plain adds cost a few turns each.
+      const unsigned long long todo = __ballot(mine);
+      const unsigned d0 = (unsigned)__builtin_amdgcn_readfirstlane((int)dg);
+      if (todo != 0ull && __ballot(mine && dg != d0) == 0ull && (todo & 1ull)) {
+        if ((threadIdx.x & 63) == 0) atomicAdd(&lh[d0], (unsigned)__popcll(todo));
+        mine = false;
+      }
+      if (mine) atomicAdd(&lh[dg], 1u);
+    }
   }
   __syncthreads();
   unsigned* out = hist + (bh * 3 + pass) * kBins;
@@ -229,8 +233,15 @@ __global__ __launch_bounds__(256) void scan_rows_kernel(const int32_t* __restric
   }
 }
 
-// One wavefront per row: write the kept columns in ascending order at the row's offset.
+// One wavefront per row: write the kept columns in ascending order at the row's offset.  KPL > 0: the row
+// (at most 64 KPL columns) is read once and its keys stay in registers, lane l holding columns l, l + 64, ...;
+// KPL == 0: rows of any length, read again where needed.
+// The counts of the row (above / equal to the threshold) say what it keeps: everything from the threshold
+// up, everything above it, or (the one row per head where the budget runs out among equal keys, or a row
+// that keeps only its best column) the keys above plus the first few equal ones.
+template <int KPL>
 __global__ __launch_bounds__(64) void fill_rows_kernel(const float* __restrict__ scores, const SelState* __restrict__ state,
+                                                       const int32_t* __restrict__ above, const int32_t* __restrict__ equal,
                                                        const int32_t* __restrict__ row_ptr, int32_t* __restrict__ cols,
                                                        uint8_t* __restrict__ mask, int g, long long cap) {
   const long long row = blockIdx.x;
@@ -238,50 +249,90 @@ __global__ __launch_bounds__(64) void fill_rows_kernel(const float* __restrict__
   const int i_row = (int)(row - bh * g);
   const int lane = threadIdx.x;
   const float* in = scores + row * g;
+  unsigned key[KPL > 0 ? KPL : 1];
+  if (KPL > 0) {
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) {
+      const int j = lane + 64 * i;
+      key[i] = j < g ? gkey(in[j]) : 0u;              // a column past the end: key 0
+    }
+  }
+  auto key_at = [&](int i) -> unsigned {              // key of column lane + 64 i (0 past the end)
+    if (KPL > 0) return key[i];
+    const int j = lane + 64 * i;
+    return j < g ? gkey(in[j]) : 0u;
+  };
+  const int n_it = (g + 63) >> 6;
   const int32_t* rp = row_ptr + bh * (g + 1) + i_row;
   const int begin = rp[0], cnt = rp[1] - rp[0];
   int32_t* out = cols + bh * cap + begin;
   uint8_t* mrow = mask ? mask + row * g : nullptr;
   unsigned thr = state[bh].prefix;
-  // first pass: keys above the threshold, and the row's largest key
-  int gt = 0;
-  unsigned best = 0u;
-  for (int j0 = 0; j0 < g; j0 += 256) {
-    float x[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int j = j0 + 64 * i + lane;
-      x[i] = j < g ? in[j] : 0.f;
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int j = j0 + 64 * i + lane;
-      const unsigned key = j < g ? gkey(x[i]) : 0u;
-      gt += __popcll(__ballot(j < g && key > thr));
-      best = max(best, key);
-    }
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) best = max(best, (unsigned)__shfl_xor((int)best, o));
+  const int gt = above[row], eq = equal[row];
   int need_eq = cnt - gt;                              // keys equal to the threshold that this row takes (its first ones)
-  if (best < thr) {                                    // nothing reaches the threshold: the first of the row's best
+  bool in_order = need_eq != 0 && need_eq != eq;       // some of the equal keys, but not all: go by column order
+  if (gt + eq == 0) {                                  // nothing reaches the threshold: the first of the row's best
+    unsigned best = 0u;
+    if (KPL > 0) {
+#pragma unroll
+      for (int i = 0; i < KPL; ++i) best = max(best, key[i]);
+    } else {
+      for (int i = 0; i < n_it; ++i) best = max(best, key_at(i));
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) best = max(best, (unsigned)__shfl_xor((int)best, o));
     thr = best;
     need_eq = 1;
+    in_order = true;
   }
+  // all equal keys, or none of them: one comparison per key.  (A threshold key of 0 is a NaN's: then the
+  // columns past the end, whose key is 0 too, need the careful path.)
+  const unsigned lo = need_eq == 0 ? thr + 1u : thr;
+  if (lo == 0u) in_order = true;
   int written = 0, eq_seen = 0;
-  for (int j0 = 0; j0 < g; j0 += 64) {
-    const int j = j0 + lane;
-    const unsigned key = j < g ? gkey(in[j]) : 0u;
-    const bool is_gt = j < g && key > thr;
-    const bool is_eq = j < g && key == thr;
-    const unsigned long long eq_mask = __ballot(is_eq);
-    const bool take = is_gt || (is_eq && eq_seen + lanes_below(eq_mask) < need_eq);
+  auto place_fast = [&](int i) {
+    const int j = lane + 64 * i;
+    const bool take = key_at(i) >= lo;
     const unsigned long long take_mask = __ballot(take);
     const int at = written + lanes_below(take_mask);
     if (take && at < cnt) out[at] = j;                 // (at < cnt always holds: the offsets were made from the same counts)
     if (mrow && j < g) mrow[j] = take ? 1 : 0;
     written += __popcll(take_mask);
+  };
+  auto place_in_order = [&](int i) {
+    const int j = lane + 64 * i;
+    const unsigned kk = key_at(i);
+    const bool is_gt = j < g && kk > thr;
+    const bool is_eq = j < g && kk == thr;
+    const unsigned long long eq_mask = __ballot(is_eq);
+    const bool take = is_gt || (is_eq && eq_seen + lanes_below(eq_mask) < need_eq);
+    const unsigned long long take_mask = __ballot(take);
+    const int at = written + lanes_below(take_mask);
+    if (take && at < cnt) out[at] = j;
+    if (mrow && j < g) mrow[j] = take ? 1 : 0;
+    written += __popcll(take_mask);
     eq_seen += __popcll(eq_mask);
+  };
+  if (!in_order) {
+    if (KPL > 0) {
+#pragma unroll
+      for (int i = 0; i < KPL; ++i) {
+        if (i >= n_it) break;                          // uniform
+        place_fast(i);
+      }
+    } else {
+      for (int i = 0; i < n_it; ++i) place_fast(i);
+    }
+  } else {
+    if (KPL > 0) {
+#pragma unroll
+      for (int i = 0; i < KPL; ++i) {
+        if (i >= n_it) break;
+        place_in_order(i);
+      }
+    } else {
+      for (int i = 0; i < n_it; ++i) place_in_order(i);
+    }
   }
 }
 
@@ -307,16 +358,26 @@ hipError_t launch_select_global(const Geo& q, long long budget, long long cap, c
   int32_t* equal = (int32_t*)(base + off);
   const long long words = bh * 3 * kBins + bh * 2;     // the histograms and, right behind them, the search state
   hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, s, hist, words);
-  const unsigned chunks = (unsigned)((g2 + kChunk - 1) / kChunk);
+  const long long per_group = (long long)kChunk * kChunksPerGroup;
+  const unsigned chunks = (unsigned)((g2 + per_group - 1) / per_group);
   for (int pass = 0; pass < 3; ++pass) {
-    hipLaunchKernelGGL(hist_kernel, dim3(chunks, (unsigned)bh), dim3(kHistThreads), 0, s, scores, hist, state, g2, pass);
+    const dim3 grid(chunks, (unsigned)bh);
+    if (pass == 0) hipLaunchKernelGGL(hist_kernel<0>, grid, dim3(kHistThreads), 0, s, scores, hist, state, g2);
+    if (pass == 1) hipLaunchKernelGGL(hist_kernel<1>, grid, dim3(kHistThreads), 0, s, scores, hist, state, g2);
+    if (pass == 2) hipLaunchKernelGGL(hist_kernel<2>, grid, dim3(kHistThreads), 0, s, scores, hist, state, g2);
     hipLaunchKernelGGL(resolve_kernel, dim3((unsigned)bh), dim3(256), 0, s, hist, state, pass, (unsigned)budget);
   }
   const unsigned rows = (unsigned)(bh * q.g);
   hipLaunchKernelGGL(count_rows_kernel, dim3(rows), dim3(64), 0, s, scores, state, above, equal, q.g);
   hipLaunchKernelGGL(scan_rows_kernel, dim3((unsigned)bh), dim3(256), 0, s, above, equal, row_ptr, q.g, (unsigned)budget,
                      (int)cap);
-  hipLaunchKernelGGL(fill_rows_kernel, dim3(rows), dim3(64), 0, s, scores, state, row_ptr, cols, mask, q.g, cap);
+  auto fill = [&](auto kernel) {
+    hipLaunchKernelGGL(kernel, dim3(rows), dim3(64), 0, s, scores, state, above, equal, row_ptr, cols, mask, q.g, cap);
+  };
+  if (q.g <= 64 * 16) fill(fill_rows_kernel<16>);
+  else if (q.g <= 64 * 32) fill(fill_rows_kernel<32>);
+  else if (q.g <= 64 * 64) fill(fill_rows_kernel<64>);
+  else fill(fill_rows_kernel<0>);
   return hipGetLastError();
 }
 

@@ -74,10 +74,11 @@ def test_select_global_on_oracle_logits(torch_mod, cases, name):
 
 def test_select_global_planted(torch_mod):
     """Maps with many equal scores (also at the threshold), rows under the threshold, signed zeros, infinities;
-    budgets from one entry to the whole map; g across several chunks of the histogram pass and ragged tails."""
+    budgets from one entry to the whole map; g across several chunks of the histogram pass and ragged tails, and
+    across the row lengths that the fill kernel treats differently (up to 1024, 2048, 4096 columns, and beyond)."""
     torch = torch_mod
     rng = np.random.default_rng(11)
-    for (g, k) in [(7, 1), (7, 7), (64, 5), (65, 33), (200, 37), (1000, 100), (1980, 198)]:
+    for (g, k) in [(7, 1), (7, 7), (64, 5), (65, 33), (200, 37), (1000, 100), (1980, 198), (2500, 20), (4200, 9)]:
         say(f"select_global planted g={g} k={k}")
         L = np.stack([rng.normal(size=(g, g)).astype(np.float32) for _ in range(3)])[None]
         L[0, 0] = np.round(L[0, 0] * 2) / 2             # head 0: duplicates everywhere, ties at the threshold
