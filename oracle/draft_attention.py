@@ -10,6 +10,7 @@ What follows the paper where:
   reorder_index        Algorithm 1 (Generate Reorder Index), plus the padding reading
   restore_index        Algorithm 2 (Generate Restore Index)
   pool_*               Definition 3.2, the two average-pooling equations
+  pool_max_f32         the max-pooling kernel of the ablation (Section 4.3): same regions, max instead of mean
   draft_logits_*, draft_map   Definition 3.2, the draft attention map equation
   select_blocks        "Guided Sparsity via Draft Attention" paragraph (top entries kept)
   select_blocks_global the threshold form of the mask, Section 3.2.2 "Error from Sparsity Mask"
@@ -178,6 +179,22 @@ def pool_canonical_f32(X32, perm, valid, block):
     return acc / valid.astype(np.float32)[:, None]
 
 
+def pool_max_f32(X32, perm, valid, block):
+    """Max over the valid tokens of each block (the ablation's downsampling kernel, Section 4.3),
+    float32 in, float32 out: exact, no rounding.  Taken slot by slot, acc = x if x > acc else acc,
+    starting from the block's first token, so a tie between -0 and +0 keeps the earlier one."""
+    g = len(valid)
+    pm = perm.reshape(g, block)
+    acc = X32[pm[:, 0]].astype(np.float32).copy()        # slot 0 of every block is a real token
+    for s in range(1, block):
+        live = valid > s
+        if not live.any():
+            break
+        x = X32[pm[live, s]]
+        acc[live] = np.where(x > acc[live], x, acc[live])
+    return acc
+
+
 # ----------------------------------------------------------------------------
 # Definition 3.2: draft map
 # ----------------------------------------------------------------------------
@@ -324,7 +341,8 @@ def sparse_attention_blocks(Qp64, Kp64, Vp64, idx, valid, block, rows=None, want
 # ----------------------------------------------------------------------------
 # the whole path for one head
 # ----------------------------------------------------------------------------
-def forward_head(Q, K, V, dtype, T, fh, fw, ph, pw, sparsity=0.0, keep_blocks=0, rows=None, whole_map=False):
+def forward_head(Q, K, V, dtype, T, fh, fw, ph, pw, sparsity=0.0, keep_blocks=0, rows=None, whole_map=False,
+                 max_pool=False):
     """pool -> draft logits (canonical float32) -> top-k -> reorder -> sparse attention
     -> restore, for one head.  Q, K, V are stored [N, d] arrays (float32 values or bf16
     bit patterns).  Returns a dict with every intermediate.  ``rows`` as above (the
@@ -336,8 +354,9 @@ def forward_head(Q, K, V, dtype, T, fh, fw, ph, pw, sparsity=0.0, keep_blocks=0,
     perm, valid = reorder_index(T, fh, fw, ph, pw)
     inv = restore_index(perm, n)
     q32, k32 = widen_f32(Q, dtype), widen_f32(K, dtype)
-    qp32 = pool_canonical_f32(q32, perm, valid, block)
-    kp32 = pool_canonical_f32(k32, perm, valid, block)
+    pool = pool_max_f32 if max_pool else pool_canonical_f32
+    qp32 = pool(q32, perm, valid, block)
+    kp32 = pool(k32, perm, valid, block)
     L32 = draft_logits_canonical_f32(qp32, kp32)
     row_ptr = cols = None
     if whole_map:

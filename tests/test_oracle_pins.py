@@ -148,6 +148,32 @@ def test_pool_matches_strided_average_pool_when_divisible():
     assert np.allclose(got32, ref, rtol=2e-6, atol=2e-6)
 
 
+def test_max_pool_hand_example_library_pool_and_special_cases():
+    # the ablation's kernel (Section 4.3): the same regions, max instead of mean
+    perm, valid = oa.reorder_index(1, 3, 3, 2, 2)
+    X = np.float32([5, 1, 7, 0, 9, 2, 3, 8, 4])[:, None]              # 3x3 frame, 2x2 window, worked by hand
+    assert list(oa.pool_max_f32(X, perm, valid, 4)[:, 0]) == [9.0, 7.0, 8.0, 4.0]
+    # divisible frames: a library max-pool with stride = window
+    import torch
+    T, fh, fw, ph, pw, d = 2, 16, 24, 8, 8, 5
+    X = _rng(31).normal(size=(T * fh * fw, d)).astype(np.float32)
+    perm, valid = oa.reorder_index(T, fh, fw, ph, pw)
+    x = torch.from_numpy(X).reshape(T, fh, fw, d).permute(0, 3, 1, 2)
+    ref = torch.nn.functional.max_pool2d(x, (ph, pw)).permute(0, 2, 3, 1).reshape(-1, d).numpy()
+    assert np.array_equal(oa.pool_max_f32(X, perm, valid, ph * pw), ref)
+    # ragged frames: only real tokens count, also where they are all negative (a zero pad would win otherwise)
+    T, fh, fw = 2, 11, 13
+    X = -np.abs(_rng(32).normal(size=(T * fh * fw, 3))).astype(np.float32) - 1.0
+    perm, valid = oa.reorder_index(T, fh, fw, 8, 8)
+    got = oa.pool_max_f32(X, perm, valid, 64)
+    for i in range(len(valid)):
+        assert np.array_equal(got[i], X[perm[i * 64:i * 64 + valid[i]]].max(axis=0))
+    assert (got < 0).all()
+    # 1x1 window: identity
+    perm1, valid1 = oa.reorder_index(T, fh, fw, 1, 1)
+    assert np.array_equal(oa.pool_max_f32(X, perm1, valid1, 1), X)
+
+
 def test_pool_canonical_order_is_sequential_float32():
     # values chosen so that float32 summation order matters: sequential slot order gives a
     # different answer from pairwise; the oracle must give the sequential one
