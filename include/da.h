@@ -41,6 +41,9 @@ extern "C" {
 #endif
 
 enum { DA_F32 = 0, DA_BF16 = 1 };
+/* How a region is pooled for the draft map: the mean (Definition 3.2), or the maximum (the other downsampling kernel
+ * of the ablation, Section 4.3: per channel the largest value among the region's valid tokens). */
+enum { DA_POOL_AVG = 0, DA_POOL_MAX = 1 };
 
 typedef enum da_status {
   DA_OK = 0,
@@ -61,6 +64,8 @@ typedef struct da_problem {
   int32_t dtype;       /* DA_F32 or DA_BF16: storage type of Q, K, V, O and their reordered copies */
   int32_t keep_blocks; /* > 0: k given explicitly (clamped to g), `sparsity` ignored; 0: use `sparsity` */
   double  sparsity;    /* fraction of key blocks dropped per query block, in [0,1); the paper's r = 1 - sparsity */
+  int32_t pool;        /* DA_POOL_AVG (0) or DA_POOL_MAX: what q_pool and k_pool hold, hence what the draft map ranks */
+  int32_t reserved;    /* 0 */
 } da_problem;
 
 typedef struct da_dims {
@@ -108,7 +113,7 @@ int da_build_perm(const da_problem* p, int32_t* perm, int32_t* inv, int32_t* val
  * Definition 3.2.  From Q and K [B,H,N,d] compute
  *   q_pool, k_pool [B,H,g,d] float : mean over the valid tokens of each block, float32,
  *       summed in slot order (acc = acc + x, one rounding per add) and divided once by
- *       the valid count;
+ *       the valid count (DA_POOL_MAX: their maximum instead, exact);
  *   logits [B,H,g,g] float : Q~ K~^T / sqrt(d) in float32 with the fixed order
  *       acc = acc + (q[c]*k[c]) for c = 0..d-1 (multiply and add rounded separately),
  *       then one multiply by float(1/sqrt(d));

@@ -19,6 +19,7 @@ DA_REORDER_ROWS, DA_REORDER_VT, DA_RESTORE, DA_REORDER_VOP = 0, 1, 2, 3
 def v_layout(dtype: int) -> int:
     """The da_permute mode that writes V the way da_sparse_attn wants it for this dtype."""
     return DA_REORDER_VOP if dtype == DA_BF16 else DA_REORDER_VT
+DA_POOL_AVG, DA_POOL_MAX = 0, 1
 DA_OK = 0
 
 EXPORTS = ["da_derive", "da_workspace_size", "da_build_perm", "da_draft_map", "da_select_blocks",
@@ -30,7 +31,8 @@ PROBE_EXPORTS = ["da_probe_mfma_bf16", "da_probe_copy"]      # include/da_probe.
 class da_problem(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("T", ctypes.c_int32), ("fh", ctypes.c_int32),
                 ("fw", ctypes.c_int32), ("d", ctypes.c_int32), ("ph", ctypes.c_int32), ("pw", ctypes.c_int32),
-                ("dtype", ctypes.c_int32), ("keep_blocks", ctypes.c_int32), ("sparsity", ctypes.c_double)]
+                ("dtype", ctypes.c_int32), ("keep_blocks", ctypes.c_int32), ("sparsity", ctypes.c_double),
+                ("pool", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class da_dims(ctypes.Structure):
@@ -89,8 +91,8 @@ def status_string(status: int) -> str:
     return lib().da_status_string(int(status)).decode()
 
 
-def problem(B, H, T, fh, fw, d, ph=8, pw=8, dtype=DA_BF16, sparsity=0.0, keep_blocks=0) -> da_problem:
-    return da_problem(B, H, T, fh, fw, d, ph, pw, dtype, keep_blocks, float(sparsity))
+def problem(B, H, T, fh, fw, d, ph=8, pw=8, dtype=DA_BF16, sparsity=0.0, keep_blocks=0, pool=DA_POOL_AVG) -> da_problem:
+    return da_problem(B, H, T, fh, fw, d, ph, pw, dtype, keep_blocks, float(sparsity), int(pool), 0)
 
 
 def problem_of(w) -> da_problem:

@@ -14,11 +14,12 @@ int check_problem(const da_problem* p, Geo* out) {
     return DA_ERR_DIM;
   if (p->dtype != DA_F32 && p->dtype != DA_BF16) return DA_ERR_DIM;
   if (p->keep_blocks < 0) return DA_ERR_DIM;
+  if (p->pool != DA_POOL_AVG && p->pool != DA_POOL_MAX) return DA_ERR_DIM;
   if (p->keep_blocks == 0 && !(p->sparsity >= 0.0 && p->sparsity < 1.0)) return DA_ERR_DIM;  // also rejects NaN
   if ((long long)p->ph * p->pw > 4096) return DA_ERR_DIM;
   Geo q;
   q.B = p->B; q.H = p->H; q.T = p->T; q.fh = p->fh; q.fw = p->fw; q.d = p->d;
-  q.ph = p->ph; q.pw = p->pw; q.dtype = p->dtype;
+  q.ph = p->ph; q.pw = p->pw; q.dtype = p->dtype; q.pool = p->pool;
   q.gh = (p->fh + p->ph - 1) / p->ph;
   q.gw = (p->fw + p->pw - 1) / p->pw;
   long long g = (long long)p->T * q.gh * q.gw;

@@ -12,6 +12,7 @@ struct Geo {
   int ph, pw, gh, gw;
   int g, block, k;
   int dtype;
+  int pool;          // DA_POOL_AVG / DA_POOL_MAX
   long long n, n_pad;
 };
 

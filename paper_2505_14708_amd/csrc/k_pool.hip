@@ -1,4 +1,5 @@
-// Average pooling of Q and K inside each latent frame (Definition 3.2).
+// Average pooling of Q and K inside each latent frame (Definition 3.2); with MAXP the maximum instead
+// (the other downsampling kernel of the ablation, Section 4.3).
 // HBM-bound: Q and K are read once in 16-byte pieces straight from the original layout
 // (the tokens of a patch row are contiguous); each lane owns a fixed group of channels of
 // one block and adds the block's tokens in slot order, so the float32 result does not
@@ -37,7 +38,7 @@ constexpr int kPoolThreads = 64;
 // grid.x covers (bh, block, chunk) items; grid.y = 0 for Q, 1 for K.  With REORDER the tokens are
 // also written, as they go by, to their slots of the reordered tensors Qp, Kp (Algorithm 1), pad
 // slots zeroed: pooling and reordering then read Q and K once between them.
-template <int DT, bool REORDER>
+template <int DT, bool REORDER, bool MAXP>
 __global__ __launch_bounds__(kPoolThreads) void pool_kernel(Geo q, const uint4* __restrict__ Q, const uint4* __restrict__ K,
                                                    float* __restrict__ q_pool, float* __restrict__ k_pool,
                                                    uint4* __restrict__ Qp, uint4* __restrict__ Kp, int cpr,
@@ -58,7 +59,12 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(Geo q, const uint4* 
   uint4* dstp = wr ? dbase + (blk * q.block) * cpr + c : nullptr;   // slot 0 of the block
   float acc[N];
 #pragma unroll
-  for (int j = 0; j < N; ++j) acc[j] = 0.f;
+  for (int j = 0; j < N; ++j) acc[j] = MAXP ? -INFINITY : 0.f;
+  // one token's channels go into the running sum, or (MAXP) replace the running maximum where larger
+  auto take = [&](const float (&f)[N]) {
+#pragma unroll
+    for (int j = 0; j < N; ++j) acc[j] = MAXP ? (f[j] > acc[j] ? f[j] : acc[j]) : acc[j] + f[j];
+  };
   int u = 0;
   // two full patch rows at a time where the patch is 8 wide: sixteen independent loads in flight,
   // added in slot order
@@ -73,8 +79,7 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(Geo q, const uint4* 
         if (wr) dstp[(long long)(u * 8 + t) * cpr] = r[t];
         float f[N];
         Vec<DT>::widen(r[t], f);
-#pragma unroll
-        for (int j = 0; j < N; ++j) acc[j] = acc[j] + f[j];
+        take(f);
       }
     }
   }
@@ -90,8 +95,7 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(Geo q, const uint4* 
         if (wr) dstp[(long long)(u * b.vw + v + t) * cpr] = r[t];
         float f[N];
         Vec<DT>::widen(r[t], f);
-#pragma unroll
-        for (int j = 0; j < N; ++j) acc[j] = acc[j] + f[j];
+        take(f);
       }
     }
     for (; v < b.vw; ++v) {
@@ -99,8 +103,7 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(Geo q, const uint4* 
       if (wr) dstp[(long long)(u * b.vw + v) * cpr] = rv;
       float f[N];
       Vec<DT>::widen(rv, f);
-#pragma unroll
-      for (int j = 0; j < N; ++j) acc[j] = acc[j] + f[j];
+      take(f);
     }
   }
   if (wr)
@@ -108,7 +111,7 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(Geo q, const uint4* 
   float cnt = (float)(b.vh * b.vw);
   float* dst = out + blk * q.d + c * N;
 #pragma unroll
-  for (int j = 0; j < N; ++j) dst[j] = acc[j] / cnt;   // IEEE division (correctly rounded is the compiler default for HIP)
+  for (int j = 0; j < N; ++j) dst[j] = MAXP ? acc[j] : acc[j] / cnt;   // IEEE division (correctly rounded is the compiler default for HIP)
 }
 
 hipError_t launch_pool(const Geo& q, const void* Q, const void* K, float* q_pool, float* k_pool, hipStream_t s) {
@@ -123,14 +126,21 @@ hipError_t launch_pool_reorder(const Geo& q, const void* Q, const void* K, float
   long long items = (long long)q.B * q.H * q.g * cpr;
   dim3 grid((unsigned)((items + kPoolThreads - 1) / kPoolThreads), 2);
   const bool re = Qp != nullptr || Kp != nullptr;
-#define DA_POOL_LAUNCH(DT, RE)                                                                                        \
-  hipLaunchKernelGGL((pool_kernel<DT, RE>), grid, dim3(kPoolThreads), 0, s, q, (const uint4*)Q, (const uint4*)K, q_pool, \
-                     k_pool, (uint4*)Qp, (uint4*)Kp, cpr, items)
+  const bool mx = q.pool == DA_POOL_MAX;
+#define DA_POOL_LAUNCH(DT, RE, MX)                                                                                    \
+  hipLaunchKernelGGL((pool_kernel<DT, RE, MX>), grid, dim3(kPoolThreads), 0, s, q, (const uint4*)Q, (const uint4*)K,  \
+                     q_pool, k_pool, (uint4*)Qp, (uint4*)Kp, cpr, items)
+#define DA_POOL_PICK(DT)                                          \
+  if (re && mx) DA_POOL_LAUNCH(DT, true, true);                   \
+  else if (re) DA_POOL_LAUNCH(DT, true, false);                   \
+  else if (mx) DA_POOL_LAUNCH(DT, false, true);                   \
+  else DA_POOL_LAUNCH(DT, false, false)
   if (q.dtype == DA_BF16) {
-    if (re) DA_POOL_LAUNCH(DA_BF16, true); else DA_POOL_LAUNCH(DA_BF16, false);
+    DA_POOL_PICK(DA_BF16);
   } else {
-    if (re) DA_POOL_LAUNCH(DA_F32, true); else DA_POOL_LAUNCH(DA_F32, false);
+    DA_POOL_PICK(DA_F32);
   }
+#undef DA_POOL_PICK
 #undef DA_POOL_LAUNCH
   return hipGetLastError();
 }

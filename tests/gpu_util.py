@@ -64,8 +64,9 @@ def vop_to_rows(vo: np.ndarray, g: int, d: int, block: int = 64) -> np.ndarray:
 class HeadRef:
     """Oracle intermediates for one head of a workload (computed lazily, cached)."""
 
-    def __init__(self, w: W.Workload, q, k, v, keep_blocks=0):
+    def __init__(self, w: W.Workload, q, k, v, keep_blocks=0, max_pool=False):
         self.w, self.q, self.k, self.v = w, q, k, v
+        self._pool = oa.pool_max_f32 if max_pool else oa.pool_canonical_f32
         self.dims = oa.derive_dims(w.T, w.fh, w.fw, w.ph, w.pw, w.sparsity, keep_blocks)
         self.perm, self.valid = oa.reorder_index(w.T, w.fh, w.fw, w.ph, w.pw)
         self.inv = oa.restore_index(self.perm, self.dims["n"])
@@ -82,13 +83,11 @@ class HeadRef:
 
     @property
     def q_pool(self):
-        return self._get("qp", lambda: oa.pool_canonical_f32(oa.widen_f32(self.q, self.w.dtype), self.perm,
-                                                             self.valid, self.block))
+        return self._get("qp", lambda: self._pool(oa.widen_f32(self.q, self.w.dtype), self.perm, self.valid, self.block))
 
     @property
     def k_pool(self):
-        return self._get("kp", lambda: oa.pool_canonical_f32(oa.widen_f32(self.k, self.w.dtype), self.perm,
-                                                             self.valid, self.block))
+        return self._get("kp", lambda: self._pool(oa.widen_f32(self.k, self.w.dtype), self.perm, self.valid, self.block))
 
     @property
     def logits(self):

@@ -402,6 +402,43 @@ def test_forward_end_to_end(torch_mod, cases, name):
                        O2.view(torch.int16 if w.dtype == W.BF16 else torch.int32))
 
 
+@pytest.mark.parametrize("name", ["tiny_fp32", "bf16_480p_T3", "f32_ragged", "bf16_8x16_ragged"])
+def test_max_pool_draft_and_forward(torch_mod, cases, name):
+    """The ablation's downsampling kernel (Section 4.3): maximum over a region instead of its mean.
+    Pooled values, logits and kept lists bit for bit; the output of the whole path within tolerance."""
+    torch = torch_mod
+    w, Q, K, V, _ = cases[name]
+    say(f"max-pool {name}")
+    p = da.problem(w.B, w.H, w.T, w.fh, w.fw, w.d, w.ph, w.pw, w.dtype, w.sparsity, pool=da.DA_POOL_MAX)
+    dims = da.da_derive(p)
+    g = dims.g
+    refs = {(b, h): HeadRef(w, Q[b, h], K[b, h], V[b, h], max_pool=True) for b in range(w.B) for h in range(w.H)}
+    qp = torch.empty((w.B, w.H, g, w.d), dtype=torch.float32, device="cuda")
+    kp = torch.empty_like(qp)
+    logits = torch.empty((w.B, w.H, g, g), dtype=torch.float32, device="cuda")
+    dQ, dK, dV = (to_dev(x, w.dtype) for x in (Q, K, V))
+    da.da_draft_map(p, dQ, dK, qp, kp, logits, None)
+    ws = torch.empty(da.da_workspace_size(p), dtype=torch.uint8, device="cuda")
+    O = empty((w.B, w.H, dims.n, w.d), w.dtype)
+    idx = torch.full((w.B, w.H, g, dims.k), -1, dtype=torch.int32, device="cuda")
+    da.da_forward(p, dQ, dK, dV, O, ws, idx)
+    torch.cuda.synchronize()
+    got = to_host_f64(O, w.dtype)
+    tol_max, tol_mean = TOL[w.dtype]
+    differs = 0
+    for (b, h), ref in refs.items():
+        assert np.array_equal(qp.cpu().numpy()[b, h].view(np.uint32), ref.q_pool.view(np.uint32))
+        assert np.array_equal(kp.cpu().numpy()[b, h].view(np.uint32), ref.k_pool.view(np.uint32))
+        assert np.array_equal(logits.cpu().numpy()[b, h].view(np.uint32), ref.logits.view(np.uint32))
+        assert np.array_equal(idx.cpu().numpy()[b, h], ref.idx)
+        differs += int(not np.array_equal(ref.idx, HeadRef(w, Q[b, h], K[b, h], V[b, h]).idx))
+        emax, emean = output_error(got[b, h], oa.restore(ref.attention(), ref.inv))
+        say(f"  {name} head {(b, h)}: max-abs {emax:.3e} mean-abs {emean:.3e}")
+        assert emax <= tol_max and emean <= tol_mean
+    if dims.k < g:
+        assert differs > 0          # the two pooling kernels do not pick the same blocks
+
+
 def test_forward_keep_one_block(torch_mod, cases):
     """k = 1: every query block attends to the single best key block (argmax, lowest index on ties)."""
     torch = torch_mod

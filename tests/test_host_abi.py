@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_struct_layout_matches_header():
-    assert ctypes.sizeof(da.da_problem) == 48 and da.da_problem.sparsity.offset == 40
+    assert ctypes.sizeof(da.da_problem) == 56 and da.da_problem.sparsity.offset == 40 and da.da_problem.pool.offset == 48
     assert ctypes.sizeof(da.da_dims) == 40 and da.da_dims.n.offset == 24
     assert ctypes.sizeof(da.da_global_dims) == 32 and da.da_global_dims.select_ws.offset == 16
 
@@ -63,7 +63,7 @@ def test_bad_problems_are_rejected():
     bad = [da.problem(0, 1, 1, 8, 8, 128), da.problem(1, 1, 1, 8, 8, 0), da.problem(1, 1, 1, 8, 8, 128, ph=0),
            da.problem(1, 1, 1, 8, 8, 128, sparsity=1.0), da.problem(1, 1, 1, 8, 8, 128, sparsity=-0.1),
            da.problem(1, 1, 1, 8, 8, 128, sparsity=float("nan")), da.problem(1, 1, 1, 8, 8, 128, dtype=7),
-           da.problem(1, 1, 1, 8, 8, 128, keep_blocks=-1), da.problem(1, 1, 100000, 4000, 4000, 128)]
+           da.problem(1, 1, 1, 8, 8, 128, keep_blocks=-1), da.problem(1, 1, 1, 8, 8, 128, pool=2), da.problem(1, 1, 100000, 4000, 4000, 128)]
     for p in bad:
         assert _status(da.da_derive, p) == -2
         assert _status(da.da_workspace_size, p) == -2
