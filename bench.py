@@ -211,6 +211,18 @@ def main():
     pe[1].record()
     torch.cuda.synchronize()
     copy_measured = 4 * 2.0 * csrc.numel() / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9
+    # a plain read of Q and K one after the other (more than the last-level cache holds)
+    ksrc = dK.view(torch.uint8).flatten()
+    da.da_probe_read(csrc, csrc.numel(), sink)
+    torch.cuda.synchronize()
+    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    pe[0].record()
+    for _ in range(2):
+        da.da_probe_read(csrc, csrc.numel(), sink)
+        da.da_probe_read(ksrc, ksrc.numel(), sink)
+    pe[1].record()
+    torch.cuda.synchronize()
+    read_measured = 2 * (csrc.numel() + ksrc.numel()) / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9
     del cdst, sink
 
     out = {
@@ -236,7 +248,7 @@ def main():
         "stages_ms": stage_ms,
         "hbm_stages": {"reorder_qkv_GBs": reorder_bytes / (stage_ms["reorder_qkv"] * 1e-3) / 1e9,
                        "restore_GBs": restore_bytes / (stage_ms["restore"] * 1e-3) / 1e9, "peak_GBs": PEAK_HBM_GBS,
-                       "measured_copy_GBs": copy_measured},
+                       "measured_copy_GBs": copy_measured, "measured_read_GBs": read_measured},
     }
     if whole_map:
         torch.cuda.synchronize()

@@ -175,6 +175,26 @@ int da_forward(const da_problem* p, const void* Q, const void* K, const void* V,
                int32_t* idx_out, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Where the rows of a caller's [B, H, rows, d] tensor live, for tensors that are not contiguous in that order (the
+ * views of a fused [B, N, 3, H, d] projection, say): elements between consecutive batches, heads and rows.  A row
+ * of d elements is contiguous; every stride is a multiple of 16 bytes and stride_n >= d.
+ */
+typedef struct da_layout {
+  int64_t stride_b, stride_h, stride_n;
+} da_layout;
+
+/*
+ * da_forward for other layouts of Q, K, V (`in`, one layout for the three) and O (`out`); NULL means contiguous
+ * [B, H, rows, d].  reordered = 0: rows are the N tokens in the original order, as in da_forward.  reordered = 1:
+ * the caller keeps its activations in the order of Algorithm 1 from layer to layer (Section 3.3's reordering is a
+ * fixed permutation of the tokens, so it can be done once per model instead of once per attention): rows are the
+ * n_pad slots, pad rows of Q, K, V must be zero, O's pad rows are left untouched (bf16) or unspecified, and a
+ * contiguous K is used where it is.  Same support matrix, workspace and result as da_forward.
+ */
+int da_forward_ex(const da_problem* p, const da_layout* in, const da_layout* out, int reordered, const void* Q,
+                  const void* K, const void* V, void* O, int32_t* idx_out, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * The whole-map form of the guided sparsity (Section 3.2.2, "Error from Sparsity Mask"): the threshold t is the
  * ceil(r g^2)-th largest score of a head's g x g map and M_ij = 1 where the score reaches t, so a row keeps as many
  * key blocks as it has scores above the threshold.  Readings: r = 1 - sparsity and the budget is

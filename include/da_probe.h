@@ -1,5 +1,5 @@
 /*
- * da_probe.h - two measuring sticks for bench.py: what the machine in front of us actually
+ * da_probe.h - three measuring sticks for bench.py: what the machine in front of us actually
  * sustains, next to its published peaks.  For callers that report a fraction of roofline and
  * want the measured ceiling beside the nominal one; not part of the attention path.
  */
@@ -26,6 +26,12 @@ int da_probe_mfma_bf16(int iters, float* sink, double* flop, void* stream);
  * 16-byte loads and stores: bytes read + bytes written = 2 * bytes.  Only enqueues.
  */
 int da_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
+
+/*
+ * A plain read of `bytes` bytes (a multiple of 16; DEVICE pointer, 16-byte aligned) with 16-byte loads, eight in
+ * flight per lane; what was read is folded into checksums in sink (DEVICE, at least 2^20 floats).  Only enqueues.
+ */
+int da_probe_read(const void* src, size_t bytes, float* sink, void* stream);
 
 #ifdef __cplusplus
 }

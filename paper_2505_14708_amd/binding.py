@@ -23,9 +23,9 @@ DA_POOL_AVG, DA_POOL_MAX = 0, 1
 DA_OK = 0
 
 EXPORTS = ["da_derive", "da_workspace_size", "da_build_perm", "da_draft_map", "da_select_blocks",
-           "da_permute", "da_sparse_attn", "da_forward", "da_global_sizes", "da_select_blocks_global",
+           "da_permute", "da_sparse_attn", "da_forward", "da_forward_ex", "da_global_sizes", "da_select_blocks_global",
            "da_sparse_attn_lists", "da_forward_global", "da_status_string"]
-PROBE_EXPORTS = ["da_probe_mfma_bf16", "da_probe_copy"]      # include/da_probe.h
+PROBE_EXPORTS = ["da_probe_mfma_bf16", "da_probe_copy", "da_probe_read"]      # include/da_probe.h
 
 
 class da_problem(ctypes.Structure):
@@ -43,6 +43,10 @@ class da_dims(ctypes.Structure):
 class da_global_dims(ctypes.Structure):
     _fields_ = [("budget", ctypes.c_int64), ("cap", ctypes.c_int64), ("select_ws", ctypes.c_size_t),
                 ("forward_ws", ctypes.c_size_t)]
+
+
+class da_layout(ctypes.Structure):
+    _fields_ = [("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64)]
 
 
 class DaError(RuntimeError):
@@ -71,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.da_permute.argtypes = [P, V, V, ctypes.c_int, V]
         L.da_sparse_attn.argtypes = [P, V, V, V, V, V, V, V]
         L.da_forward.argtypes = [P, V, V, V, V, V, V, ctypes.c_size_t, V]
+        L.da_forward_ex.argtypes = [P, ctypes.POINTER(da_layout), ctypes.POINTER(da_layout), ctypes.c_int, V, V, V, V, V, V,
+                                    ctypes.c_size_t, V]
         L.da_global_sizes.argtypes = [P, ctypes.POINTER(da_global_dims)]
         L.da_select_blocks_global.argtypes = [P, V, V, V, V, V, ctypes.c_size_t, V]
         L.da_sparse_attn_lists.argtypes = [P, V, V, V, V, V, ctypes.c_int64, V, V, V]
@@ -79,6 +85,8 @@ def lib() -> ctypes.CDLL:
         L.da_probe_mfma_bf16.restype = ctypes.c_int
         L.da_probe_copy.argtypes = [V, V, ctypes.c_size_t, V]
         L.da_probe_copy.restype = ctypes.c_int
+        L.da_probe_read.argtypes = [V, ctypes.c_size_t, V, V]
+        L.da_probe_read.restype = ctypes.c_int
         L.da_status_string.argtypes = [ctypes.c_int]
         L.da_status_string.restype = ctypes.c_char_p
         for name in EXPORTS[:-1]:
@@ -164,6 +172,20 @@ def da_forward(p, Q, K, V, O, ws, idx_out=None, stream=None):
                             ctypes.c_size_t(nbytes), _stream(stream)), "da_forward")
 
 
+def layout_of(t) -> da_layout:
+    """da_layout of a torch tensor viewed as [B, H, rows, d] (any strides, d contiguous)."""
+    assert t.dim() == 4 and t.stride(3) == 1
+    return da_layout(t.stride(0), t.stride(1), t.stride(2))
+
+
+def da_forward_ex(p, Q, K, V, O, ws, layout_in=None, layout_out=None, reordered=0, idx_out=None, stream=None):
+    nbytes = ws.numel() * ws.element_size()
+    li = ctypes.byref(layout_in) if layout_in is not None else None
+    lo = ctypes.byref(layout_out) if layout_out is not None else None
+    _check(lib().da_forward_ex(ctypes.byref(p), li, lo, int(reordered), _ptr(Q), _ptr(K), _ptr(V), _ptr(O),
+                               _ptr(idx_out), _ptr(ws), ctypes.c_size_t(nbytes), _stream(stream)), "da_forward_ex")
+
+
 def da_global_sizes(p: da_problem) -> da_global_dims:
     out = da_global_dims()
     _check(lib().da_global_sizes(ctypes.byref(p), ctypes.byref(out)), "da_global_sizes")
@@ -198,3 +220,7 @@ def da_probe_mfma_bf16(iters: int, sink, stream=None) -> float:
 
 def da_probe_copy(src, dst, nbytes: int, stream=None):
     _check(lib().da_probe_copy(_ptr(src), _ptr(dst), ctypes.c_size_t(int(nbytes)), _stream(stream)), "da_probe_copy")
+
+
+def da_probe_read(src, nbytes: int, sink, stream=None):
+    _check(lib().da_probe_read(_ptr(src), ctypes.c_size_t(int(nbytes)), _ptr(sink), _stream(stream)), "da_probe_read")

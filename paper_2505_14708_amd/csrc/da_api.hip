@@ -41,6 +41,10 @@ int check_problem(const da_problem* p, Geo* out) {
   if (k < 1) k = 1;
   if (k > g) k = g;
   q.k = (int)k;
+  // contiguous [B, H, N, d] in the original order unless an entry point says otherwise
+  q.in.sn = q.d; q.in.sh = q.n * q.d; q.in.sb = (long long)q.H * q.n * q.d;
+  q.out = q.in;
+  q.reordered = 0;
   *out = q;
   return DA_OK;
 }
@@ -194,11 +198,38 @@ int da_sparse_attn(const da_problem* p, const void* Qp, const void* Kp, const vo
 }
 
 // da_forward and da_forward_global: the same launches but for the selection
-static int forward_impl(const da_problem* p, bool whole_map, const void* Q, const void* K, const void* V, void* O,
-                        int32_t* idx_out, int32_t* row_ptr_out, void* ws, size_t ws_bytes, void* stream) {
+// in / out: where the caller's Q, K, V and O live (NULL: contiguous); reordered: their rows are the slots of
+// Algorithm 1's order instead of tokens
+static int set_layout(Geo& q, const da_layout* in, const da_layout* out, int reordered) {
+  if (reordered != 0 && reordered != 1) return DA_ERR_DIM;
+  q.reordered = reordered;
+  const long long rows = reordered ? q.n_pad : q.n;
+  const long long per = q.dtype == DA_BF16 ? 8 : 4;   // elements per 16 bytes
+  Rows dflt;
+  dflt.sn = q.d; dflt.sh = rows * q.d; dflt.sb = (long long)q.H * rows * q.d;
+  q.in = q.out = dflt;
+  const da_layout* given[2] = {in, out};
+  Rows* into[2] = {&q.in, &q.out};
+  for (int t = 0; t < 2; ++t) {
+    if (!given[t]) continue;
+    const da_layout& l = *given[t];
+    if (l.stride_n < q.d || l.stride_h < 1 || l.stride_b < 1) return DA_ERR_DIM;
+    if (l.stride_n % per || l.stride_h % per || l.stride_b % per) return DA_ERR_ALIGN;
+    // the last element must be addressable with 63-bit offsets, with room to spare
+    if ((double)q.B * (double)l.stride_b + (double)q.H * (double)l.stride_h + (double)rows * (double)l.stride_n > 4.0e15)
+      return DA_ERR_DIM;
+    into[t]->sb = l.stride_b; into[t]->sh = l.stride_h; into[t]->sn = l.stride_n;
+  }
+  return DA_OK;
+}
+
+static int forward_impl(const da_problem* p, bool whole_map, const da_layout* in, const da_layout* out, int reordered,
+                        const void* Q, const void* K, const void* V, void* O, int32_t* idx_out, int32_t* row_ptr_out,
+                        void* ws, size_t ws_bytes, void* stream) {
   Geo q;
   int st = check_problem(p, &q);
   if (st != DA_OK) return st;
+  if ((st = set_layout(q, in, out, reordered)) != DA_OK) return st;
   if (!Q || !K || !V || !O || !ws) return DA_ERR_NULL;
   if (whole_map && (idx_out == nullptr) != (row_ptr_out == nullptr)) return DA_ERR_NULL;   // both or neither
   if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(idx_out) ||
@@ -228,7 +259,12 @@ static int forward_impl(const da_problem* p, bool whole_map, const void* Q, cons
   // not copied at all: the attention kernel reads its query rows from their original places and
   // writes O's rows back to theirs, which is Algorithm 1 for Q and Algorithm 2 for O done by
   // addressing (a row of 256 bytes is contiguous in either order).
-  if ((e = launch_pool_reorder(q, Q, K, q_pool, k_pool, bf16 ? nullptr : qp, kp, s)) != hipSuccess) return DA_ERR_HIP;
+  // (K that already is a contiguous reordered tensor is used where it is.)
+  const bool k_in_place = bf16 && q.reordered && q.in.sn == q.d && q.in.sh == q.n_pad * q.d &&
+                          q.in.sb == (long long)q.H * q.n_pad * q.d;
+  if (k_in_place) kp = const_cast<void*>(K);
+  if ((e = launch_pool_reorder(q, Q, K, q_pool, k_pool, bf16 ? nullptr : qp, k_in_place ? nullptr : kp, s)) != hipSuccess)
+    return DA_ERR_HIP;
   if ((e = launch_draft_logits(q, q_pool, k_pool, logits, s)) != hipSuccess) return DA_ERR_HIP;
   // guided sparsity: k per row, or the threshold over the whole map (Section 3.2.2)
   if (whole_map)
@@ -248,7 +284,12 @@ static int forward_impl(const da_problem* p, bool whole_map, const void* Q, cons
 
 int da_forward(const da_problem* p, const void* Q, const void* K, const void* V, void* O, int32_t* idx_out,
                void* ws, size_t ws_bytes, void* stream) {
-  return forward_impl(p, false, Q, K, V, O, idx_out, nullptr, ws, ws_bytes, stream);
+  return forward_impl(p, false, nullptr, nullptr, 0, Q, K, V, O, idx_out, nullptr, ws, ws_bytes, stream);
+}
+
+int da_forward_ex(const da_problem* p, const da_layout* in, const da_layout* out, int reordered, const void* Q,
+                  const void* K, const void* V, void* O, int32_t* idx_out, void* ws, size_t ws_bytes, void* stream) {
+  return forward_impl(p, false, in, out, reordered, Q, K, V, O, idx_out, nullptr, ws, ws_bytes, stream);
 }
 
 int da_global_sizes(const da_problem* p, da_global_dims* out) {
@@ -298,7 +339,7 @@ int da_sparse_attn_lists(const da_problem* p, const void* Qp, const void* Kp, co
 
 int da_forward_global(const da_problem* p, const void* Q, const void* K, const void* V, void* O, int32_t* row_ptr_out,
                       int32_t* cols_out, void* ws, size_t ws_bytes, void* stream) {
-  return forward_impl(p, true, Q, K, V, O, cols_out, row_ptr_out, ws, ws_bytes, stream);
+  return forward_impl(p, true, nullptr, nullptr, 0, Q, K, V, O, cols_out, row_ptr_out, ws, ws_bytes, stream);
 }
 
 const char* da_status_string(int status) {

@@ -6,6 +6,12 @@
 
 namespace da {
 
+// Where the rows of a [B, H, rows, d] tensor of the caller live: offsets in elements between consecutive
+// batches, heads and rows (a row of d elements is contiguous).
+struct Rows {
+  long long sb, sh, sn;
+};
+
 // Everything the kernels need to know about one problem (passed by value).
 struct Geo {
   int B, H, T, fh, fw, d;
@@ -14,7 +20,17 @@ struct Geo {
   int dtype;
   int pool;          // DA_POOL_AVG / DA_POOL_MAX
   long long n, n_pad;
+  // The caller's Q, K, V (in) and O (out).  reordered == 0: rows are tokens in the original order
+  // (n per head); 1: rows are the slots of Algorithm 1's order (n_pad per head, pad rows zero).
+  Rows in, out;
+  int reordered;
 };
+
+// element offset of row `row` of (batch, head) number bh
+__host__ __device__ inline long long row_offset(const Rows& r, int H, long long bh, long long row) {
+  const long long b = bh / H, h = bh - b * H;
+  return b * r.sb + h * r.sh + row * r.sn;
+}
 
 // Block i (in Algorithm 1's frame / patch-row / patch-column order) -> its frame, the
 // token coordinates of its top-left corner and its valid extent.
@@ -40,6 +56,13 @@ __host__ __device__ inline int block_valid(const Geo& q, int i) {
   BlockPos b = block_pos(q, i);
   return b.vh * b.vw;
 }
+
+// First row of block i in the caller's Q, K, V, O (slot 0 of the block) and the distance in rows between the
+// block's patch rows: slot s = u * vw + v of the block is row first + u * pitch + v.
+__host__ __device__ inline long long block_first_row(const Geo& q, int i, const BlockPos& b) {
+  return q.reordered ? (long long)i * q.block : ((long long)b.f * q.fh + b.y0) * q.fw + b.x0;
+}
+__host__ __device__ inline int block_row_pitch(const Geo& q, const BlockPos& b) { return q.reordered ? b.vw : q.fw; }
 
 // Original token index -> slot in the reordered sequence (pi^-1 of Algorithm 2).
 __host__ __device__ inline long long token_slot(const Geo& q, long long n) {

@@ -373,21 +373,23 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
 
   // Q fragments (B operand): lane (query r, half-wave hh) holds d = 16t + 8hh .. +7.  Asked for
   // first, so that they arrive while the lists are being merged.
-  // With `direct`, Qp and Op are Q and O in the original token order: the reordering of Q and the
-  // restoring of O (Algorithms 1 and 2) are then this kernel's addressing, slot -> token.
+  // With `direct`, Qp and Op are the caller's Q and O (q.in, q.out: in the original token order as a rule): the
+  // reordering of Q and the restoring of O (Algorithms 1 and 2) are then this kernel's addressing, slot -> row.
   const BlockPos qpos = block_pos(q, has_block ? my_block : 0);
-  // row of slot s of my query block in Qp / Op, or -1 (pad slot of the original order)
-  auto row_of = [&](int s) -> long long {
-    if (!direct) return qb * BLOCK + s;
+  const long long q_first = block_first_row(q, has_block ? my_block : 0, qpos);
+  const int q_pitch = block_row_pitch(q, qpos);
+  // byte offset of the row of slot s of my query block in Qp / Op, or -1 (a pad slot has no row of its own there)
+  auto row_bytes = [&](int s, const Rows& where) -> long long {
+    if (!direct) return (qb * BLOCK + s) * (long long)(D * 2);
     if (s >= qpos.vh * qpos.vw) return -1;
     const int u = s / qpos.vw, v = s - u * qpos.vw;
-    return bh * q.n + ((long long)qpos.f * q.fh + qpos.y0 + u) * q.fw + qpos.x0 + v;
+    return row_offset(where, q.H, bh, q_first + (long long)u * q_pitch + v) * 2;
   };
   bf16x8 qf[8];
   {
     const int r = lane & 31, hh = lane >> 5;
-    const long long row = row_of(32 * part + r);
-    const unsigned char* qrow = Qp + max(row, 0LL) * (D * 2);
+    const long long row = row_bytes(32 * part + r, q.in);
+    const unsigned char* qrow = Qp + max(row, 0LL);
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
       qf[t] = *(const bf16x8*)(qrow + (16 * t + 8 * hh) * 2);
@@ -749,8 +751,8 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
 #pragma unroll
   for (int it = 0; it < 8; ++it) {
     const int row = it * 4 + (lane >> 4), ch = lane & 15;
-    const long long orow = row_of(32 * part + row);
-    if (orow >= 0) *(uint4*)(Op + orow * (D * 2) + ch * 16) = *(const uint4*)(stage + row * O_STRIDE + ch * 16);
+    const long long orow = row_bytes(32 * part + row, q.out);
+    if (orow >= 0) *(uint4*)(Op + orow + ch * 16) = *(const uint4*)(stage + row * O_STRIDE + ch * 16);
   }
 }
 

@@ -27,6 +27,8 @@ __global__ void build_perm_kernel(Geo q, int32_t* perm, int32_t* inv, int32_t* v
 
 // One workgroup per (block, batch*head).  cpr = 16-byte chunks per row.
 // FWD: Y[slot] = X[pi[slot]] or zeros;  !FWD: X-order output, Y[token] = Xp[slot].
+// The reordered side is contiguous [B,H,n_pad,d]; the other side is the caller's tensor (q.in for
+// the source of FWD, q.out for the destination of !FWD).
 template <bool FWD>
 __global__ __launch_bounds__(256) void permute_rows_kernel(Geo q, const chunk16* __restrict__ X, chunk16* __restrict__ Y,
                                                             int cpr) {
@@ -34,10 +36,11 @@ __global__ __launch_bounds__(256) void permute_rows_kernel(Geo q, const chunk16*
   long long bh = blockIdx.y;
   BlockPos b = block_pos(q, i);
   int nv = b.vh * b.vw;
-  const long long src_bh = bh * (FWD ? q.n : q.n_pad) * cpr;
-  const long long dst_bh = bh * (FWD ? q.n_pad : q.n) * cpr;
-  long long slot0 = (long long)i * q.block;
-  long long tok0 = ((long long)b.f * q.fh + b.y0) * q.fw + b.x0;
+  const int per = q.d / cpr;                           // elements per chunk
+  const Rows& far = FWD ? q.in : q.out;
+  const long long far0 = row_offset(far, q.H, bh, block_first_row(q, i, b)) / per;   // chunk of the block's first row
+  const long long far_sn = far.sn / per, pitch = block_row_pitch(q, b);
+  const long long near0 = (bh * q.n_pad + (long long)i * q.block) * cpr;
   int total = (FWD ? q.block : nv) * cpr;
   for (int e = threadIdx.x; e < total; e += blockDim.x) {
     int s = e / cpr, c = e - s * cpr;
@@ -45,12 +48,12 @@ __global__ __launch_bounds__(256) void permute_rows_kernel(Geo q, const chunk16*
       chunk16 val = make_uint4(0, 0, 0, 0);
       if (s < nv) {
         int u = s / b.vw, v = s - u * b.vw;
-        val = X[src_bh + (tok0 + (long long)u * q.fw + v) * cpr + c];
+        val = X[far0 + ((long long)u * pitch + v) * far_sn + c];
       }
-      Y[dst_bh + (slot0 + s) * cpr + c] = val;
+      Y[near0 + (long long)s * cpr + c] = val;
     } else {
       int u = s / b.vw, v = s - u * b.vw;
-      Y[dst_bh + (tok0 + (long long)u * q.fw + v) * cpr + c] = X[src_bh + (slot0 + s) * cpr + c];
+      Y[far0 + ((long long)u * pitch + v) * far_sn + c] = X[near0 + (long long)s * cpr + c];
     }
   }
 }
@@ -71,14 +74,14 @@ __global__ __launch_bounds__(256) void permute_vt_kernel(Geo q, const E* __restr
   BlockPos b = block_pos(q, i);
   int nv = b.vh * b.vw;
   int cpr = q.d / PER;
-  long long tok0 = ((long long)b.f * q.fh + b.y0) * q.fw + b.x0;
-  const chunk16* Xc = (const chunk16*)(X + bh * q.n * q.d);
+  const chunk16* Xc = (const chunk16*)(X + row_offset(q.in, q.H, bh, block_first_row(q, i, b)));   // the block's first row
+  const long long sn = q.in.sn / PER, pitch = block_row_pitch(q, b);
   for (int e = threadIdx.x; e < q.block * cpr; e += blockDim.x) {
     int s = e / cpr, c = e - s * cpr;
     chunk16 val = make_uint4(0, 0, 0, 0);
     if (s < nv) {
       int u = s / b.vw, v = s - u * b.vw;
-      val = Xc[(tok0 + (long long)u * q.fw + v) * cpr + c];
+      val = Xc[((long long)u * pitch + v) * sn + c];
     }
     *(chunk16*)(tile + s * ld + c * PER) = val;
   }

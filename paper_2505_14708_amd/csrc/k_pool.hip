@@ -53,7 +53,10 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(Geo q, const uint4* 
   long long bh = blk / q.g;
   int i = (int)(blk - bh * q.g);
   BlockPos b = block_pos(q, i);
-  const uint4* src = X + (bh * q.n + ((long long)b.f * q.fh + b.y0) * q.fw + b.x0) * cpr + c;
+  // chunks between consecutive rows of the source, rows between the block's patch rows
+  const long long sn = q.in.sn / N;
+  const long long pitch = block_row_pitch(q, b);
+  const uint4* src = X + row_offset(q.in, q.H, bh, block_first_row(q, i, b)) / N + c;
   uint4* const dbase = blockIdx.y ? Kp : Qp;          // NULL: this tensor is only pooled
   const bool wr = REORDER && dbase != nullptr;
   uint4* dstp = wr ? dbase + (blk * q.block) * cpr + c : nullptr;   // slot 0 of the block
@@ -70,10 +73,10 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(Geo q, const uint4* 
   // added in slot order
   if (b.vw == 8) {
     for (; u + 2 <= b.vh; u += 2) {
-      const uint4* row = src + (long long)u * q.fw * cpr;
+      const uint4* row = src + (long long)u * pitch * sn;
       uint4 r[16];
 #pragma unroll
-      for (int t = 0; t < 16; ++t) r[t] = row[((long long)(t >> 3) * q.fw + (t & 7)) * cpr];
+      for (int t = 0; t < 16; ++t) r[t] = row[((long long)(t >> 3) * pitch + (t & 7)) * sn];
 #pragma unroll
       for (int t = 0; t < 16; ++t) {
         if (wr) dstp[(long long)(u * 8 + t) * cpr] = r[t];
@@ -84,12 +87,12 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(Geo q, const uint4* 
     }
   }
   for (; u < b.vh; ++u) {
-    const uint4* row = src + (long long)u * q.fw * cpr;
+    const uint4* row = src + (long long)u * pitch * sn;
     int v = 0;
     for (; v + 8 <= b.vw; v += 8) {  // eight independent loads in flight, added in order
       uint4 r[8];
 #pragma unroll
-      for (int t = 0; t < 8; ++t) r[t] = row[(long long)(v + t) * cpr];
+      for (int t = 0; t < 8; ++t) r[t] = row[(long long)(v + t) * sn];
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
         if (wr) dstp[(long long)(u * b.vw + v + t) * cpr] = r[t];
@@ -99,7 +102,7 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(Geo q, const uint4* 
       }
     }
     for (; v < b.vw; ++v) {
-      const uint4 rv = row[(long long)v * cpr];
+      const uint4 rv = row[(long long)v * sn];
       if (wr) dstp[(long long)(u * b.vw + v) * cpr] = rv;
       float f[N];
       Vec<DT>::widen(rv, f);

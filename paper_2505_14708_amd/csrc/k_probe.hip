@@ -50,6 +50,25 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const uint4* __restrict
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
 
+// a plain read: every lane keeps eight 16-byte loads in flight and folds what it read into one word
+__global__ __launch_bounds__(256) void probe_read_kernel(const uint4* __restrict__ src, unsigned* __restrict__ sink, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  unsigned acc = 0u;
+  for (; i + 7 * stride < n16; i += 8 * stride) {
+    uint4 r[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) r[t] = src[i + t * stride];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc ^= r[t].x ^ r[t].y ^ r[t].z ^ r[t].w;
+  }
+  for (; i < n16; i += stride) {
+    const uint4 r = src[i];
+    acc ^= r.x ^ r.y ^ r.z ^ r.w;
+  }
+  sink[(blockIdx.x * 256u + threadIdx.x) & ((1u << 20) - 1u)] = acc;
+}
+
 }  // namespace
 
 extern "C" {
@@ -67,6 +86,15 @@ int da_probe_copy(const void* src, void* dst, size_t bytes, void* stream) {
   if (bytes == 0 || bytes % 16 != 0) return DA_ERR_DIM;
   if (((uintptr_t)src & 15u) || ((uintptr_t)dst & 15u)) return DA_ERR_ALIGN;
   hipLaunchKernelGGL(probe_copy_kernel, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, (uint4*)dst,
+                     bytes / 16);
+  return hipGetLastError() == hipSuccess ? DA_OK : DA_ERR_HIP;
+}
+
+int da_probe_read(const void* src, size_t bytes, float* sink, void* stream) {
+  if (!src || !sink) return DA_ERR_NULL;
+  if (bytes == 0 || bytes % 16 != 0) return DA_ERR_DIM;
+  if ((uintptr_t)src & 15u) return DA_ERR_ALIGN;
+  hipLaunchKernelGGL(probe_read_kernel, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, (unsigned*)sink,
                      bytes / 16);
   return hipGetLastError() == hipSuccess ? DA_OK : DA_ERR_HIP;
 }

@@ -439,6 +439,66 @@ def test_max_pool_draft_and_forward(torch_mod, cases, name):
         assert differs > 0          # the two pooling kernels do not pick the same blocks
 
 
+@pytest.mark.parametrize("name", ["bf16_480p_T3", "f32_ragged", "bf16_B2_T5", "bf16_8x16_ragged"])
+def test_forward_ex_layouts(torch_mod, cases, name):
+    """Other layouts of the caller's tensors: the views of a fused [B, N, 3, H, d] projection with O as [B, N, H, d];
+    activations kept in the order of Algorithm 1 (contiguous, and as [B, n_pad, H, d]).  Same lists and the same
+    output bits as da_forward on contiguous tensors, which the other tests hold against the oracle; one head is
+    compared with the oracle here as well."""
+    torch = torch_mod
+    w, Q, K, V, refs = cases[name]
+    say(f"forward_ex {name}")
+    p = da.problem_of(w)
+    dims = da.da_derive(p)
+    as_int = torch.int16 if w.dtype == W.BF16 else torch.int32
+    ws = torch.empty(da.da_workspace_size(p), dtype=torch.uint8, device="cuda")
+    dQ, dK, dV = (to_dev(x, w.dtype) for x in (Q, K, V))
+    O = empty((w.B, w.H, dims.n, w.d), w.dtype)
+    idx = torch.empty((w.B, w.H, dims.g, dims.k), dtype=torch.int32, device="cuda")
+    da.da_forward(p, dQ, dK, dV, O, ws, idx)
+    torch.cuda.synchronize()
+    # 1. token-major fused projection
+    fused = empty((w.B, dims.n, 3, w.H, w.d), w.dtype)
+    for t, x in enumerate((dQ, dK, dV)):
+        fused[:, :, t] = x.permute(0, 2, 1, 3)
+    q4, k4, v4 = (fused[:, :, t].permute(0, 2, 1, 3) for t in range(3))
+    O_tok = empty((w.B, dims.n, w.H, w.d), w.dtype)
+    o4 = O_tok.permute(0, 2, 1, 3)
+    idx2 = torch.empty_like(idx)
+    da.da_forward_ex(p, q4, k4, v4, o4, ws, da.layout_of(q4), da.layout_of(o4), 0, idx2)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2)
+    assert torch.equal(o4.contiguous().view(as_int), O.view(as_int))
+    ref = refs[(0, 0)]
+    emax, emean = output_error(to_host_f64(o4.contiguous(), w.dtype)[0, 0], oa.restore(ref.attention(), ref.inv))
+    assert emax <= TOL[w.dtype][0] and emean <= TOL[w.dtype][1]
+    # 2. activations in the order of Algorithm 1, contiguous [B, H, n_pad, d]
+    Qp, Kp, Vp = (empty((w.B, w.H, dims.n_pad, w.d), w.dtype) for _ in range(3))
+    for x, xp in ((dQ, Qp), (dK, Kp), (dV, Vp)):
+        da.da_permute(p, x, xp, da.DA_REORDER_ROWS)
+    Op = empty((w.B, w.H, dims.n_pad, w.d), w.dtype)
+    Op.fill_(7.0)
+    idx3 = torch.empty_like(idx)
+    da.da_forward_ex(p, Qp, Kp, Vp, Op, ws, None, None, 1, idx3)
+    back = torch.empty_like(O)
+    da.da_permute(p, Op, back, da.DA_RESTORE)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx3)
+    assert torch.equal(back.view(as_int), O.view(as_int))
+    if w.dtype == W.BF16:
+        pad = torch.from_numpy(ref.perm < 0).cuda()
+        assert (Op[:, :, pad] == 7.0).all()              # pad rows of O are left alone
+    # 3. the same, slot-major [B, n_pad, H, d]
+    q5, k5, v5 = (x.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for x in (Qp, Kp, Vp))
+    O5 = empty((w.B, dims.n_pad, w.H, w.d), w.dtype)
+    o5 = O5.permute(0, 2, 1, 3)
+    da.da_forward_ex(p, q5, k5, v5, o5, ws, da.layout_of(q5), da.layout_of(o5), 1, None)
+    back5 = torch.empty_like(O)
+    da.da_permute(p, o5.contiguous(), back5, da.DA_RESTORE)
+    torch.cuda.synchronize()
+    assert torch.equal(back5.view(as_int), O.view(as_int))
+
+
 def test_forward_keep_one_block(torch_mod, cases):
     """k = 1: every query block attends to the single best key block (argmax, lowest index on ties)."""
     torch = torch_mod

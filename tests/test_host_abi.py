@@ -140,6 +140,27 @@ def test_global_sizes_match_oracle_and_checks():
     assert L.da_forward_global(*args, V(FAKE), None, V(FAKE), ctypes.c_size_t(sz.forward_ws), None) == -1   # one of the two
 
 
+def test_forward_ex_layout_checks():
+    p = da.problem_of(W.CONFIGS["480p"])
+    need = da.da_workspace_size(p)
+    L = da.lib()
+    V = ctypes.c_void_p
+
+    def call(lin, lout, reordered):
+        li = ctypes.byref(lin) if lin is not None else None
+        lo = ctypes.byref(lout) if lout is not None else None
+        return L.da_forward_ex(ctypes.byref(p), li, lo, reordered, V(FAKE), V(FAKE), V(FAKE), V(FAKE), None, V(FAKE + 16),
+                               ctypes.c_size_t(need), None)
+    d = 128
+    good = da.da_layout(10 ** 9, d, 3 * 24 * d)
+    assert call(good, good, 0) == -5                                   # gets as far as the workspace alignment check
+    assert call(good, good, 2) == -2                                   # reordered is 0 or 1
+    assert call(da.da_layout(10 ** 9, d, d - 8), None, 0) == -2        # rows overlap
+    assert call(da.da_layout(10 ** 9, d + 4, 3 * d), None, 0) == -5    # not a multiple of 16 bytes
+    assert call(None, da.da_layout(0, d, d), 1) == -2
+    assert ctypes.sizeof(da.da_layout) == 24
+
+
 def test_status_strings():
     assert da.status_string(0) == "ok"
     for s in range(-6, 0):
