@@ -210,7 +210,7 @@ typedef struct da_global_dims {
   size_t forward_ws;  /* bytes of scratch da_forward_global needs */
 } da_global_dims;
 
-/* Host only, pure. */
+/* Host only, pure.  DA_ERR_DIM when cap does not fit int32 or g^2 >= 2^32. */
 int da_global_sizes(const da_problem* p, da_global_dims* out /* host */);
 
 /*

@@ -66,9 +66,11 @@ inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Entries kept by the whole-map selection (Section 3.2.2: ceil(r g^2), here g^2 - floor(sparsity g^2 + 1e-6);
 // k per row given explicitly means the same total, k g) and the room to allocate per (batch, head): a row the
-// threshold leaves empty keeps one column, so up to g more.  Returns false when the offsets do not fit int32.
+// threshold leaves empty keeps one column, so up to g more.  Returns false when the offsets do not fit int32
+// (or a head's map has 2^32 entries or more).
 bool global_budget(const da_problem* p, const Geo& q, long long* budget, long long* cap) {
   const long long g2 = (long long)q.g * q.g;
+  if (g2 > 0xffffffffLL) return false;                 // the selector counts the keys of a head in 32 bits
   long long b = p->keep_blocks > 0 ? (long long)q.k * q.g : g2 - (long long)floor(p->sparsity * (double)g2 + 1e-6);
   if (b < 1) b = 1;
   if (b > g2) b = g2;
