@@ -67,7 +67,7 @@ def cpu_baseline(w, Q, K, V, budget_s=20.0, whole_map=False):
     g = dims["g"]
     done, t_attn = 0, 0.0
     Op = None
-    order = np.linspace(0, g - 1, num=min(g, 512)).astype(int)
+    order = np.argsort((np.arange(g) * 0.6180339887498949) % 1.0, kind="stable")   # every prefix is spread evenly over the blocks
     while done < len(order) and t_attn < max(2.0, budget_s - t_fixed):
         rows = order[done:done + 8]
         t1 = time.perf_counter()

@@ -148,6 +148,50 @@ def test_sparse_attn_lists_stage(torch_mod, cases, name):
         assert lerr < (2e-2 if w.dtype == W.BF16 else 1e-4)
 
 
+def test_sparse_attn_lists_empty_and_unsorted_rows(torch_mod, cases):
+    """Lists a caller made by hand: some query blocks attend nothing (their rows come out as zeros), the others hold
+    their blocks in any order."""
+    torch = torch_mod
+    w, Q, K, V, refs = cases["bf16_B2_T5"]
+    say("sparse_attn_lists with empty rows")
+    p = da.problem_of(w)
+    dims = da.da_derive(p)
+    g = dims.g
+    rng = np.random.default_rng(12)
+    lists = {}
+    for key in refs:
+        rows = []
+        for i in range(g):
+            n = 0 if i % 7 == 3 else int(rng.integers(1, 12))
+            rows.append(rng.choice(g, size=n, replace=False).astype(np.int64))
+        lists[key] = rows
+    cap = (max(sum(len(r) for r in rows) for rows in lists.values()) + 3) // 4 * 4
+    sel = {key: (np.concatenate([[0], np.cumsum([len(r) for r in rows])]), np.concatenate(rows), None)
+           for key, rows in lists.items()}
+    row_ptr, cols = _lists_to_dev(torch, refs, w, g, cap, sel)
+    Qp = empty((w.B, w.H, dims.n_pad, w.d), w.dtype)
+    Kp = empty((w.B, w.H, dims.n_pad, w.d), w.dtype)
+    Vt = empty((w.B, w.H, dims.g, w.d, dims.block), w.dtype)
+    da.da_permute(p, to_dev(Q, w.dtype), Qp, da.DA_REORDER_ROWS)
+    da.da_permute(p, to_dev(K, w.dtype), Kp, da.DA_REORDER_ROWS)
+    da.da_permute(p, to_dev(V, w.dtype), Vt, da.v_layout(w.dtype))
+    Op = empty((w.B, w.H, dims.n_pad, w.d), w.dtype)
+    Op.fill_(7.0)
+    da.da_sparse_attn_lists(p, Qp, Kp, Vt, row_ptr, cols, cap, Op, None)
+    torch.cuda.synchronize()
+    got = to_host_f64(Op, w.dtype)
+    for (b, h), ref in refs.items():
+        full = [i for i in range(g) if len(lists[(b, h)][i])]
+        want = ref.attention(rows=full, idx=lists[(b, h)])
+        for i in range(g):
+            sl = slice(i * dims.block, i * dims.block + ref.valid[i])
+            if len(lists[(b, h)][i]) == 0:
+                assert (got[b, h][sl] == 0.0).all(), i
+            else:
+                emax, emean = output_error(got[b, h][sl], want[sl])
+                assert emax <= 2e-2 and emean <= 2.5e-3, (i, emax, emean)
+
+
 def test_sparse_attn_lists_equals_fixed_k(torch_mod, cases):
     """Lists that all hold k entries: the result of da_sparse_attn on the [g, k] table (to rounding: the walk
     over the tiles may take another order)."""
