@@ -47,8 +47,7 @@
 // change the result at the precision of the output and its exponentials and second product are
 // skipped.  With peaked attention that is the common case, so V^T operands are fetched from
 // global memory (L2) straight into registers, only by the waves that need them, while the
-// exponentials are being computed; a wave whose tiles keep mattering asks for them before the
-// first product instead.
+// exponentials are being computed.
 //
 // The running max only moves (and O is rescaled) when a row max exceeds it by more than 2^8 in
 // the exponent's units; until then probabilities are formed against the stale max, which is
@@ -83,7 +82,6 @@ constexpr float kC2 = 0.08838834764831845f * 1.4426950408889634f;   // log2(e)/s
 constexpr float kLazy = 8.0f;                     // move the running max only past this many powers of two
 constexpr float kDropLog2 = 14.0f;                // all keys dropped from a row together weigh less than 2^-14 of its largest term
 constexpr int kSpinLimit = 1 << 20;
-constexpr int kEarlyAfter = 3;                    // V is asked for ahead of the first product after this many tiles in a row mattered
 
 // ---------------------------------------------------------------------------------- tile movement
 // 16 KB tile, rows of ROWB bytes, moved 1 KB (64 lanes x 16 B) per step; step `it` covers rows
@@ -185,42 +183,12 @@ struct Soft {
 // order: the 64 lanes' operands of (k-step t, channel group dt) are the contiguous KB number
 // 4t + dt of the tile, so every load of a wave is one contiguous KB).
 __device__ __forceinline__ bool compute_tile(const unsigned char* const (&kaddr)[8], const unsigned char* vt, int hh,
-                                             int nv, bool pad_query, float skip, bool early, const bf16x8 (&qf)[8],
+                                             int nv, bool pad_query, float skip, const bf16x8 (&qf)[8],
                                              f32x16 (&o)[4], Soft& st) {
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   f32x16 s0, s1;
   bf16x8 va[4][4];
-  if (early) {
-    // The caller's last few tiles all mattered, so this one probably does (where attention is not
-    // peaked every tile does): its V^T operands are asked for before the first product and their
-    // L2 latency hides behind it.  A wrong guess costs an unused read.  The K operands then come
-    // in two halves, for want of registers.
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt) va[t][dt] = *(const bf16x8*)(vt + (t * 4 + dt) * 1024);
-    bf16x8 ka[4], kb[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      ka[t] = *(const bf16x8*)(kaddr[t]);
-      kb[t] = *(const bf16x8*)(kaddr[t] + 32 * 256);
-    }
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      s0 = mfma(ka[t], qf[t], t == 0 ? zero : s0);
-      s1 = mfma(kb[t], qf[t], t == 0 ? zero : s1);
-    }
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      ka[t] = *(const bf16x8*)(kaddr[4 + t]);
-      kb[t] = *(const bf16x8*)(kaddr[4 + t] + 32 * 256);
-    }
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      s0 = mfma(ka[t], qf[4 + t], s0);
-      s1 = mfma(kb[t], qf[4 + t], s1);
-    }
-  } else {
+  {
     // S^T = K Q^T; all sixteen K operands are asked for before the first product, so the LDS
     // latency is paid once per tile
     bf16x8 ka[8], kb[8];
@@ -250,13 +218,14 @@ __device__ __forceinline__ bool compute_tile(const unsigned char* const (&kaddr)
   // product are skipped.  (Never the first time: top is -inf.)  Pad query slots have no say: their
   // rows are zero, every score is 0, and nobody reads their output.
   if (__all(pad_query || (mx - st.top) * kC2 < -skip)) return false;
-  if (!early) {
-    // V^T operands: on their way while the exponentials are computed
+  // V^T operands: on their way while the exponentials are computed.  (Asking for them before the first product
+  // where tiles keep mattering was tried: a tile dropped after all then leaves loads in flight, the compiler has
+  // to wait for everything outstanding at the top of every tile, the ring's transfers included, and the common
+  // case lost more than the other gained.)
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+  for (int t = 0; t < 4; ++t)
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt) va[t][dt] = *(const bf16x8*)(vt + (t * 4 + dt) * 1024);
-  }
+    for (int dt = 0; dt < 4; ++dt) va[t][dt] = *(const bf16x8*)(vt + (t * 4 + dt) * 1024);
   st.top = fmaxf(st.top, mx);
   if (__any((mx - st.m) * kC2 > kLazy)) {
     const float m_new = fmaxf(st.m, mx);
@@ -653,7 +622,6 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
     pending = L;
   };
   bool gave_up = false;
-  int streak = 0;                                     // how many of my tiles in a row have mattered
   int snap = look();
   // The walk, 64 entries at a time: lane i holds entry base + i, a ballot tells which of them
   // are mine.  Entries that are not mine cost nothing: prog jumps over them.
@@ -696,9 +664,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
         const unsigned char* kaddr[8];
 #pragma unroll
         for (int t = 0; t < 8; ++t) kaddr[t] = slot + kofs[t];
-        const bool mattered = compute_tile(kaddr, Vlane + (long long)(e & 0x3fffffu) * V_TILE, hh, nv, pad_query, skip,
-                                           streak >= kEarlyAfter, qf, o, st);
-        streak = mattered ? streak + 1 : 0;
+        compute_tile(kaddr, Vlane + (long long)(e & 0x3fffffu) * V_TILE, hh, nv, pad_query, skip, qf, o, st);
       }
       // my reads of the slot are complete: leave the entry, and those up to my next one, behind
       wait_lds();
