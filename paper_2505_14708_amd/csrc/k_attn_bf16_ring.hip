@@ -35,9 +35,10 @@
 //   ready[s]   union entry whose K tile slot s holds (set once the tile has landed)
 //   prog[w]    how many entries wave w has left behind (it leaves them in order, at once if its
 //              list does not hold the entry); the slowest wave bounds what may be overwritten
-//   next_load  entries are requested strictly in order, entry L as soon as L < min(prog) + 8;
-//              whichever wave notices first claims it with a compare-and-swap, waits for the load
-//              at the top of its next trip (or while it is idle) and publishes it.
+//   next_load  entries are requested strictly in order, entry L once L < min(prog) + 8, by the waves
+//              that are waiting for a tile: the one that notices first claims it with a compare-and-
+//              swap, waits for the load (it is idle anyway, or at the top of its next trip) and
+//              publishes it.  Waves that have a tile to work on do not look for room.
 // A wave reads all of this with one LDS access per poll.  Every wait is bounded: if a tile does
 // not show up the wave gives up (its output rows are then NaN, but the kernel always ends).
 //
@@ -672,8 +673,9 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
         const int nxt = mine ? base + (int)__builtin_ctzll(mine) : min(base + 64, nU);
         if (lane == 0) __atomic_store_n(&prog[wave], nxt, __ATOMIC_RELAXED);
       }
+      // (Only waves that are waiting for a tile ask for tiles: having every wave look for room after each of
+      // its tiles cost the busy ones more than the earlier requests saved.)
       snap = fresh;
-      service(snap);
     }
   }
   publish();
