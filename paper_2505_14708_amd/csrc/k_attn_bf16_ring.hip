@@ -374,9 +374,9 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   const int bw = (g + 31) >> 5;
   unsigned* ulist = bitmap + 4 * bw;                  // union entries: key sub-block | (valid slots - 1) << 22 | membership << 28
   const int union_max = SUB * (LISTS ? g : min(g, FG * q.k));
-  int* ctrl = (int*)(smem + LDS_TOTAL - 128);         // [32]: ready[8], prog[8], next_load, count, n_own
+  int* ctrl = (int*)(smem + LDS_TOTAL - 128);         // [32]: ready[8], left[8], next_load, count, n_own, ..., live waves
   int* ready = ctrl;                                  // [RING]
-  int* prog = ctrl + 8;                               // [WAVES]
+  int* left = ctrl + 8;                               // [RING]
   int* next_load = ctrl + 16;
   int* count = ctrl + 17;                             // [2]
 
@@ -389,6 +389,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   for (int i = threadIdx.x; i < 4 * bw; i += 512) bitmap[i] = 0u;
   if (threadIdx.x < 32) ctrl[threadIdx.x] = threadIdx.x < RING ? -1 : 0;
   __syncthreads();
+  if (live && lane == 0) atomicOr(&ctrl[28], 1 << wave);   // which waves take tiles at all
   if (lister) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -570,9 +571,18 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   const unsigned char* Kbh = Kp + bh * q.n_pad * (D * 2);
   const unsigned char* Vlane = Vt + bh * q.n_pad * (D * 2) + lane * 16;
   // one wave brings the K tile of union entry u into ring slot u % RING
+  const int live_waves = __builtin_amdgcn_readfirstlane(ctrl[28]);
   auto issue_tile = [&](int u) {
-    const unsigned e = ulist[u];
-    const long long j = __builtin_amdgcn_readfirstlane((int)(e & 0x3fffffu));
+    const unsigned e = (unsigned)__builtin_amdgcn_readfirstlane((int)ulist[u]);
+    // how many waves will read the tile: the live waves of the query blocks that hold the entry
+    int readers = 0;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) {
+      const int qb_w = SUB == 1 ? (w + 2 * (w >> 2)) & 3 : w >> 2;
+      readers += (live_waves >> w) & (int)(e >> (28 + qb_w)) & 1;
+    }
+    if (lane == 0) __atomic_store_n(&left[u & (RING - 1)], readers, __ATOMIC_RELAXED);   // (before the transfer, hence before the slot is published)
+    const long long j = (long long)(e & 0x3fffffu);
     dma_tile(Kbh + j * K_TILE, ring_lds + (unsigned)(u & (RING - 1)) * SLOT, koff);
   };
   int pending = -1;
@@ -611,10 +621,10 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
     if (__builtin_amdgcn_readfirstlane(pending) >= 0) return;   // at most one request of mine in flight
     const int L = __builtin_amdgcn_readlane(c, 16);
     if (L >= nU) return;
-    int fr = __builtin_amdgcn_readlane(c, 8);
-#pragma unroll
-    for (int w = 1; w < WAVES; ++w) fr = min(fr, __builtin_amdgcn_readlane(c, 8 + w));
-    if (L >= fr + RING) return;
+    // its slot is free once every reader of the entry it holds has left it (and that entry did arrive)
+    const int sl = L & (RING - 1);
+    if (__builtin_amdgcn_readlane(c, 8 + sl) != 0) return;
+    if (L >= RING && __builtin_amdgcn_readlane(c, sl) != L - RING) return;
     int got = L + 1;
     if (lane == 0) got = atomicCAS(next_load, L, L + 1);
     got = __builtin_amdgcn_readfirstlane(got);
@@ -629,10 +639,6 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   for (int base = 0; base < nU && !gave_up; base += 64) {
     const unsigned e_lane = base + lane < nU ? ulist[base + lane] : 0u;
     unsigned long long mine = __ballot((e_lane & my_bit) != 0u);
-    {
-      const int nxt = mine ? base + (int)__builtin_ctzll(mine) : min(base + 64, nU);
-      if (lane == 0) __atomic_store_n(&prog[wave], nxt, __ATOMIC_RELAXED);
-    }
     while (mine) {
       const int i = (int)__builtin_ctzll(mine);
       mine &= mine - 1;
@@ -667,12 +673,9 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
         for (int t = 0; t < 8; ++t) kaddr[t] = slot + kofs[t];
         compute_tile(kaddr, Vlane + (long long)(e & 0x3fffffu) * V_TILE, hh, nv, pad_query, skip, qf, o, st);
       }
-      // my reads of the slot are complete: leave the entry, and those up to my next one, behind
+      // my reads of the slot are complete: one reader less
       wait_lds();
-      {
-        const int nxt = mine ? base + (int)__builtin_ctzll(mine) : min(base + 64, nU);
-        if (lane == 0) __atomic_store_n(&prog[wave], nxt, __ATOMIC_RELAXED);
-      }
+      if (lane == 0) atomicSub(&left[slot_i], 1);
       // (Only waves that are waiting for a tile ask for tiles: having every wave look for room after each of
       // its tiles cost the busy ones more than the earlier requests saved.)
       snap = fresh;
