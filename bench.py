@@ -37,7 +37,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 # HBM-side bytes per launch of the attention kernel (read, written), from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this program, scaled by what the same counters read for the row-copy kernel of known
 # size in the same run (profiles/pmc_traffic_720p_hunyuan.txt).  Workloads without a counter run: null.
-ATTN_TRAFFIC_BYTES = {"720p_hunyuan": (57.73e9, 0.754e9)}
+ATTN_TRAFFIC_BYTES = {"720p_hunyuan": (56.36e9, 0.754e9)}
 
 
 def cpu_baseline(w, Q, K, V, budget_s=20.0, whole_map=False):
