@@ -33,9 +33,10 @@
 // p ^ swizzle(r), which makes the operand reads conflict-free.  There are no workgroup barriers
 // in the tile loop:
 //   ready[s]   union entry whose K tile slot s holds (set once the tile has landed)
-//   prog[w]    how many entries wave w has left behind (it leaves them in order, at once if its
-//              list does not hold the entry); the slowest wave bounds what may be overwritten
-//   next_load  entries are requested strictly in order, entry L once L < min(prog) + 8, by the waves
+//   left[s]    how many waves have yet to read the tile in slot s (set when the tile is asked for: the
+//              live waves of the query blocks that hold the entry; every reader takes one off when it
+//              is through): at zero the slot may be overwritten
+//   next_load  entries are requested strictly in order, entry L once its slot L % 8 is free, by the waves
 //              that are waiting for a tile: the one that notices first claims it with a compare-and-
 //              swap, waits for the load (it is idle anyway, or at the top of its next trip) and
 //              publishes it.  Waves that have a tile to work on do not look for room.
@@ -635,7 +636,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   bool gave_up = false;
   int snap = look();
   // The walk, 64 entries at a time: lane i holds entry base + i, a ballot tells which of them
-  // are mine.  Entries that are not mine cost nothing: prog jumps over them.
+  // are mine.  Entries that are not mine cost nothing.
   for (int base = 0; base < nU && !gave_up; base += 64) {
     const unsigned e_lane = base + lane < nU ? ulist[base + lane] : 0u;
     unsigned long long mine = __ballot((e_lane & my_bit) != 0u);
