@@ -167,9 +167,19 @@ __device__ __forceinline__ void mask_pad_half(f32x16& s, int mt, int nv, int hh)
   }
 }
 
+// n / d for 0 <= n < 2^24, d >= 1, by way of the float reciprocal (exact: the estimate is off by one at most)
+__device__ __forceinline__ int small_div(int n, int d) {
+  int qt = (int)((float)n * __frcp_rn((float)d));
+  const int rem = n - qt * d;
+  qt += rem >= d ? 1 : 0;
+  qt -= rem < 0 ? 1 : 0;
+  return qt;
+}
+
+// valid slots of block j (blocks are numbered below 2^22)
 __device__ __forceinline__ int valid_slots(const Geo& q, int per_frame, int j) {
-  int rr = j % per_frame;
-  int bi = rr / q.gw, bj = rr - bi * q.gw;
+  const int rr = j - small_div(j, per_frame) * per_frame;
+  const int bi = small_div(rr, q.gw), bj = rr - bi * q.gw;
   return min(q.ph, q.fh - bi * q.ph) * min(q.pw, q.fw - bj * q.pw);
 }
 
@@ -308,13 +318,15 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   const int qblk = SUB == 1 ? (wave + 2 * half) & 3 : half;
   const int part = SUB == 1 ? half : wave & 3;
   // query block w of this workgroup: (position, frame), or none
+  // (divisions of small non-negative numbers: by way of the float reciprocal)
+  const int n_over_fgs = n >= 0 ? small_div(n >> 3, max(fgs, 1)) : 0;
   auto slot_pos = [&](int w) -> int {
-    if (n >= 0) return (n & 7) + 8 * ((n >> 3) / fgs);
-    return w < plan.per_wg * plan.rem ? (n + plan.tail_wgs) * plan.per_wg + w / plan.rem : per_frame;
+    if (n >= 0) return (n & 7) + 8 * n_over_fgs;
+    return w < plan.per_wg * plan.rem ? (n + plan.tail_wgs) * plan.per_wg + small_div(w, plan.rem) : per_frame;
   };
   auto slot_frame = [&](int w) -> int {
-    if (n >= 0) return FG * ((n >> 3) % fgs) + w;
-    return fgs * FG + w % plan.rem;
+    if (n >= 0) return FG * ((n >> 3) - n_over_fgs * fgs) + w;
+    return fgs * FG + (w - small_div(w, plan.rem) * plan.rem);
   };
   // block number of query block w, -1 if the slot is empty
   auto slot_block = [&](int w) -> int {
