@@ -161,6 +161,20 @@ def test_forward_ex_layout_checks():
     assert ctypes.sizeof(da.da_layout) == 24
 
 
+def test_missing_library_is_an_error_not_a_fallback(monkeypatch, tmp_path):
+    """Without the built library every call raises: nothing in the package computes on the CPU instead, and the
+    package never imports the oracle."""
+    monkeypatch.setattr(da, "_lib", None)
+    monkeypatch.setattr(da, "LIB_PATH", str(tmp_path / "libdraftattn.so"))
+    with pytest.raises(RuntimeError, match="not built"):
+        da.da_derive(da.problem_of(W.CONFIGS["tiny_fp32"]))
+    pkg = os.path.join(ROOT, "paper_2505_14708_amd")
+    for name in os.listdir(pkg):
+        if name.endswith(".py"):
+            src = open(os.path.join(pkg, name)).read()
+            assert "import oracle" not in src and "from oracle" not in src, name
+
+
 def test_status_strings():
     assert da.status_string(0) == "ok"
     for s in range(-6, 0):
