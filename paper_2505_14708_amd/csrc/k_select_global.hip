@@ -138,15 +138,22 @@ __global__ __launch_bounds__(256) void resolve_kernel(const unsigned* __restrict
   }
 }
 
-// One wavefront per row: how many keys of the row are above the threshold key, how many equal it.
+// One wavefront per row: how many keys of the row are above the threshold key, how many equal it, and which:
+// bit l of word i of the row's two bit masks is column 64 i + l.  For a row that nothing of reaches the
+// threshold, the column of its best key (the lowest one on ties) as well.
 __global__ __launch_bounds__(64) void count_rows_kernel(const float* __restrict__ scores, const SelState* __restrict__ state,
-                                                        int32_t* __restrict__ above, int32_t* __restrict__ equal, int g) {
+                                                        int32_t* __restrict__ above, int32_t* __restrict__ equal,
+                                                        unsigned long long* __restrict__ gt_bits,
+                                                        unsigned long long* __restrict__ eq_bits, int32_t* __restrict__ forced,
+                                                        int g, int W) {
   const long long row = blockIdx.x;
   const long long bh = row / g;
   const int lane = threadIdx.x;
   const unsigned thr = state[bh].prefix;
   const float* in = scores + row * g;
   int gt = 0, eq = 0;
+  unsigned best = 0u;
+  unsigned long long my_gt = 0ull, my_eq = 0ull;       // lane l keeps word 64 k + l of the current group of 64 words
   for (int j0 = 0; j0 < g; j0 += 256) {
     float x[4];
 #pragma unroll
@@ -157,14 +164,41 @@ __global__ __launch_bounds__(64) void count_rows_kernel(const float* __restrict_
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int j = j0 + 64 * i + lane;
-      const unsigned key = gkey(x[i]);
-      gt += __popcll(__ballot(j < g && key > thr));
-      eq += __popcll(__ballot(j < g && key == thr));
+      const int wi = (j0 >> 6) + i;                     // word of this step (the same in every lane)
+      const unsigned key = j < g ? gkey(x[i]) : 0u;
+      const unsigned long long bgt = __ballot(j < g && key > thr);
+      const unsigned long long beq = __ballot(j < g && key == thr);
+      gt += __popcll(bgt);
+      eq += __popcll(beq);
+      best = max(best, key);
+      if ((wi & 63) == lane) {
+        my_gt = bgt;
+        my_eq = beq;
+      }
+      if (wi < W && ((wi & 63) == 63 || wi == W - 1)) {  // a group of words is complete: one coalesced store
+        const int mine = (wi & ~63) + lane;
+        if (mine <= wi) {
+          gt_bits[row * W + mine] = my_gt;
+          eq_bits[row * W + mine] = my_eq;
+        }
+      }
     }
   }
   if (lane == 0) {
     above[row] = gt;
     equal[row] = eq;
+  }
+  if (gt + eq == 0) {                                   // (the same in every lane)
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) best = max(best, (unsigned)__shfl_xor((int)best, o));
+    for (int j0 = 0; j0 < g; j0 += 64) {
+      const int j = j0 + lane;
+      const unsigned long long hit = __ballot(j < g && gkey(in[j]) == best);
+      if (hit) {
+        if (lane == 0) forced[row] = j0 + (int)__builtin_ctzll(hit);
+        break;
+      }
+    }
   }
 }
 
@@ -233,129 +267,115 @@ __global__ __launch_bounds__(256) void scan_rows_kernel(const int32_t* __restric
   }
 }
 
-// One wavefront per row: write the kept columns in ascending order at the row's offset.  KPL > 0: the row
-// (at most 64 KPL columns) is read once and its keys stay in registers, lane l holding columns l, l + 64, ...;
-// KPL == 0: rows of any length, read again where needed.
-// The counts of the row (above / equal to the threshold) say what it keeps: everything from the threshold
-// up, everything above it, or (the one row per head where the budget runs out among equal keys, or a row
-// that keeps only its best column) the keys above plus the first few equal ones.
-template <int KPL>
-__global__ __launch_bounds__(64) void fill_rows_kernel(const float* __restrict__ scores, const SelState* __restrict__ state,
-                                                       const int32_t* __restrict__ above, const int32_t* __restrict__ equal,
-                                                       const int32_t* __restrict__ row_ptr, int32_t* __restrict__ cols,
-                                                       uint8_t* __restrict__ mask, int g, long long cap) {
+// exclusive prefix sum over the 64 lanes; *total receives the sum
+__device__ inline int lane_scan(int v, int lane, int* total) {
+  int inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int up = __shfl_up(inc, o);
+    if (lane >= o) inc += up;
+  }
+  *total = __shfl(inc, 63);
+  return inc - v;
+}
+
+// One wavefront per row: write the kept columns in ascending order at the row's offset, from the row's bit
+// masks (the scores are not read again).  Lane l takes word l of a group of 64 words: the keys above the
+// threshold, and of the equal ones the row's first need_eq, counted across the words by a lane scan.
+__global__ __launch_bounds__(64) void fill_rows_kernel(const int32_t* __restrict__ above, const int32_t* __restrict__ equal,
+                                                       const unsigned long long* __restrict__ gt_bits,
+                                                       const unsigned long long* __restrict__ eq_bits,
+                                                       const int32_t* __restrict__ forced, const int32_t* __restrict__ row_ptr,
+                                                       int32_t* __restrict__ cols, uint8_t* __restrict__ mask, int g, int W,
+                                                       long long cap) {
   const long long row = blockIdx.x;
   const long long bh = row / g;
   const int i_row = (int)(row - bh * g);
   const int lane = threadIdx.x;
-  const float* in = scores + row * g;
-  unsigned key[KPL > 0 ? KPL : 1];
-  if (KPL > 0) {
-#pragma unroll
-    for (int i = 0; i < KPL; ++i) {
-      const int j = lane + 64 * i;
-      key[i] = j < g ? gkey(in[j]) : 0u;              // a column past the end: key 0
-    }
-  }
-  auto key_at = [&](int i) -> unsigned {              // key of column lane + 64 i (0 past the end)
-    if (KPL > 0) return key[i];
-    const int j = lane + 64 * i;
-    return j < g ? gkey(in[j]) : 0u;
-  };
-  const int n_it = (g + 63) >> 6;
   const int32_t* rp = row_ptr + bh * (g + 1) + i_row;
   const int begin = rp[0], cnt = rp[1] - rp[0];
   int32_t* out = cols + bh * cap + begin;
   uint8_t* mrow = mask ? mask + row * g : nullptr;
-  unsigned thr = state[bh].prefix;
   const int gt = above[row], eq = equal[row];
-  int need_eq = cnt - gt;                              // keys equal to the threshold that this row takes (its first ones)
-  bool in_order = need_eq != 0 && need_eq != eq;       // some of the equal keys, but not all: go by column order
-  if (gt + eq == 0) {                                  // nothing reaches the threshold: the first of the row's best
-    unsigned best = 0u;
-    if (KPL > 0) {
-#pragma unroll
-      for (int i = 0; i < KPL; ++i) best = max(best, key[i]);
-    } else {
-      for (int i = 0; i < n_it; ++i) best = max(best, key_at(i));
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) best = max(best, (unsigned)__shfl_xor((int)best, o));
-    thr = best;
-    need_eq = 1;
-    in_order = true;
-  }
-  // all equal keys, or none of them: one comparison per key.  (A threshold key of 0 is a NaN's: then the
-  // columns past the end, whose key is 0 too, need the careful path.)
-  const unsigned lo = need_eq == 0 ? thr + 1u : thr;
-  if (lo == 0u) in_order = true;
+  const int need_eq = cnt - gt;
+  const bool only_best = gt + eq == 0;                  // nothing reaches the threshold: the row keeps its best column
+  const int best_col = only_best ? forced[row] : -1;
+  if (only_best && lane == 0 && cnt > 0) out[0] = best_col;
   int written = 0, eq_seen = 0;
-  auto place_fast = [&](int i) {
-    const int j = lane + 64 * i;
-    const bool take = key_at(i) >= lo;
-    const unsigned long long take_mask = __ballot(take);
-    const int at = written + lanes_below(take_mask);
-    if (take && at < cnt) out[at] = j;                 // (at < cnt always holds: the offsets were made from the same counts)
-    if (mrow && j < g) mrow[j] = take ? 1 : 0;
-    written += __popcll(take_mask);
-  };
-  auto place_in_order = [&](int i) {
-    const int j = lane + 64 * i;
-    const unsigned kk = key_at(i);
-    const bool is_gt = j < g && kk > thr;
-    const bool is_eq = j < g && kk == thr;
-    const unsigned long long eq_mask = __ballot(is_eq);
-    const bool take = is_gt || (is_eq && eq_seen + lanes_below(eq_mask) < need_eq);
-    const unsigned long long take_mask = __ballot(take);
-    const int at = written + lanes_below(take_mask);
-    if (take && at < cnt) out[at] = j;
-    if (mrow && j < g) mrow[j] = take ? 1 : 0;
-    written += __popcll(take_mask);
-    eq_seen += __popcll(eq_mask);
-  };
-  if (!in_order) {
-    if (KPL > 0) {
-#pragma unroll
-      for (int i = 0; i < KPL; ++i) {
-        if (i >= n_it) break;                          // uniform
-        place_fast(i);
-      }
-    } else {
-      for (int i = 0; i < n_it; ++i) place_fast(i);
+  for (int w0 = 0; w0 < W; w0 += 64) {
+    const int wi = w0 + lane;
+    unsigned long long G = 0ull, E = 0ull;
+    if (wi < W && !only_best) {
+      G = gt_bits[row * W + wi];
+      E = eq_bits[row * W + wi];
     }
-  } else {
-    if (KPL > 0) {
-#pragma unroll
-      for (int i = 0; i < KPL; ++i) {
-        if (i >= n_it) break;
-        place_in_order(i);
+    const int pe = __popcll(E);
+    int pe_total;
+    const int eq_before = eq_seen + lane_scan(pe, lane, &pe_total);
+    int n = need_eq - eq_before;
+    n = n < 0 ? 0 : n > pe ? pe : n;
+    unsigned long long Et = E;
+    if (n < pe) {                                       // the word where the row's share of the equal keys runs out
+      Et = 0ull;
+      unsigned long long rest = E;
+      for (int t = 0; t < n; ++t) {
+        Et |= rest & (0ull - rest);
+        rest &= rest - 1ull;
       }
-    } else {
-      for (int i = 0; i < n_it; ++i) place_in_order(i);
     }
+    unsigned long long T = G | Et;
+    if (only_best && wi == (best_col >> 6)) T = 1ull << (best_col & 63);
+    const int pt = only_best ? 0 : __popcll(T);
+    int pt_total;
+    int at = written + lane_scan(pt, lane, &pt_total);
+    if (!only_best) {
+      unsigned long long rest = T;
+      while (rest) {
+        const int bit = (int)__builtin_ctzll(rest);
+        rest &= rest - 1ull;
+        if (at < cnt) out[at] = 64 * wi + bit;          // (at < cnt always holds: the offsets were made from the same counts)
+        ++at;
+      }
+    }
+    if (mrow && wi < W)
+      for (int bit = 0; bit < 64 && 64 * wi + bit < g; ++bit) mrow[64 * wi + bit] = (uint8_t)((T >> bit) & 1ull);
+    written += pt_total;
+    eq_seen += pe_total;
   }
 }
 
 }  // namespace
 
+namespace {
+inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+}  // namespace
+
+// histograms + search state, the rows' counts, their two bit masks, the best column of rows under the threshold
 size_t select_global_workspace(const Geo& q) {
-  const size_t bh = (size_t)q.B * q.H;
-  return 256 + bh * 3 * kBins * sizeof(unsigned) + ((bh * sizeof(SelState) + 255) & ~(size_t)255) +
-         2 * ((bh * (size_t)q.g * sizeof(int32_t) + 255) & ~(size_t)255);
+  const size_t bh = (size_t)q.B * q.H, rows = bh * (size_t)q.g, W = ((size_t)q.g + 63) / 64;
+  return 256 + up256(bh * 3 * kBins * sizeof(unsigned) + bh * sizeof(SelState)) + 3 * up256(rows * sizeof(int32_t)) +
+         2 * up256(rows * W * sizeof(unsigned long long));
 }
 
 hipError_t launch_select_global(const Geo& q, long long budget, long long cap, const float* scores, int32_t* row_ptr,
                                 int32_t* cols, uint8_t* mask, void* ws, hipStream_t s) {
   const long long bh = (long long)q.B * q.H;
   const long long g2 = (long long)q.g * q.g;
+  const size_t rows_n = (size_t)bh * q.g;
+  const int W = (q.g + 63) / 64;
   char* base = (char*)ws;
   unsigned* hist = (unsigned*)base;
-  size_t off = (size_t)bh * 3 * kBins * sizeof(unsigned);
-  SelState* state = (SelState*)(base + off);
-  off += ((size_t)bh * sizeof(SelState) + 255) & ~(size_t)255;
+  SelState* state = (SelState*)(base + (size_t)bh * 3 * kBins * sizeof(unsigned));   // right behind the histograms
+  size_t off = up256((size_t)bh * 3 * kBins * sizeof(unsigned) + (size_t)bh * sizeof(SelState));
   int32_t* above = (int32_t*)(base + off);
-  off += ((size_t)bh * q.g * sizeof(int32_t) + 255) & ~(size_t)255;
+  off += up256(rows_n * sizeof(int32_t));
   int32_t* equal = (int32_t*)(base + off);
+  off += up256(rows_n * sizeof(int32_t));
+  int32_t* forced = (int32_t*)(base + off);
+  off += up256(rows_n * sizeof(int32_t));
+  unsigned long long* gt_bits = (unsigned long long*)(base + off);
+  off += up256(rows_n * W * sizeof(unsigned long long));
+  unsigned long long* eq_bits = (unsigned long long*)(base + off);
   const long long words = bh * 3 * kBins + bh * 2;     // the histograms and, right behind them, the search state
   hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, s, hist, words);
   const long long per_group = (long long)kChunk * kChunksPerGroup;
@@ -367,17 +387,13 @@ hipError_t launch_select_global(const Geo& q, long long budget, long long cap, c
     if (pass == 2) hipLaunchKernelGGL(hist_kernel<2>, grid, dim3(kHistThreads), 0, s, scores, hist, state, g2);
     hipLaunchKernelGGL(resolve_kernel, dim3((unsigned)bh), dim3(256), 0, s, hist, state, pass, (unsigned)budget);
   }
-  const unsigned rows = (unsigned)(bh * q.g);
-  hipLaunchKernelGGL(count_rows_kernel, dim3(rows), dim3(64), 0, s, scores, state, above, equal, q.g);
+  const unsigned rows = (unsigned)rows_n;
+  hipLaunchKernelGGL(count_rows_kernel, dim3(rows), dim3(64), 0, s, scores, state, above, equal, gt_bits, eq_bits, forced, q.g,
+                     W);
   hipLaunchKernelGGL(scan_rows_kernel, dim3((unsigned)bh), dim3(256), 0, s, above, equal, row_ptr, q.g, (unsigned)budget,
                      (int)cap);
-  auto fill = [&](auto kernel) {
-    hipLaunchKernelGGL(kernel, dim3(rows), dim3(64), 0, s, scores, state, above, equal, row_ptr, cols, mask, q.g, cap);
-  };
-  if (q.g <= 64 * 16) fill(fill_rows_kernel<16>);
-  else if (q.g <= 64 * 32) fill(fill_rows_kernel<32>);
-  else if (q.g <= 64 * 64) fill(fill_rows_kernel<64>);
-  else fill(fill_rows_kernel<0>);
+  hipLaunchKernelGGL(fill_rows_kernel, dim3(rows), dim3(64), 0, s, above, equal, gt_bits, eq_bits, forced, row_ptr, cols, mask,
+                     q.g, W, cap);
   return hipGetLastError();
 }
 
