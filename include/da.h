@@ -26,8 +26,9 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue work: no synchronisation, no host read-back, no allocation.
  *   - Return value: DA_OK (0) or a negative da_status.  On error nothing was launched,
- *     except DA_ERR_HIP, which reports a failed launch.  No global mutable state; calls
- *     on different streams may run concurrently if their buffers are disjoint.
+ *     except DA_ERR_HIP, which reports a failed launch.  No global mutable state (but for the
+ *     counter da_wait_failures reads); calls on different streams may run concurrently if their
+ *     buffers are disjoint.
  *   - NaN/Inf in the inputs give unspecified values but never a fault.
  */
 #ifndef DA_H
@@ -161,6 +162,26 @@ int da_permute(const da_problem* p, const void* X, void* Y, int mode, void* stre
  */
 int da_sparse_attn(const da_problem* p, const void* Qp, const void* Kp, const void* Vt,
                    const int32_t* idx, void* Op, float* lse, void* stream);
+
+/*
+ * da_sparse_attn with two extras (SparseAttn equation, Section 3.1; Algorithms 1 and 2 by addressing).
+ * original_order = 1 (DA_BF16 only): Q and O are the caller's [B,H,N,d] tensors in the ORIGINAL token order; the
+ *   kernel reads each query row from, and writes each output row to, its original place, which is what da_forward
+ *   does (Kp and Vt are still the reordered tensors; lse, if given, stays in slot order).  0: as da_sparse_attn.
+ * tile_counts (DEVICE, two uint64, may be NULL; DA_BF16 only): the kernel ADDS to [0] the number of tiles
+ *   (32 queries x 64 keys) its waves went through and to [1] the number of those whose exponentials and second
+ *   product were carried out (the others fell to the drop rule described above).  The caller clears it.  Each tile
+ *   is 16 matrix instructions for the first product and, if carried out, 16 for the second.
+ */
+int da_sparse_attn_ex(const da_problem* p, const void* Q, const void* Kp, const void* Vt, const int32_t* idx, void* O,
+                      float* lse, int original_order, uint64_t* tile_counts, void* stream);
+
+/*
+ * Host call, synchronises the current device.  count (host) receives the number of wavefronts of the bf16 attention
+ * kernel whose bounded wait for a key tile ran out (their rows were written as NaN) since the library was loaded,
+ * on the current device.  No valid input makes that happen; a caller that wants to be sure checks for 0.
+ */
+int da_wait_failures(uint64_t* count /* host */);
 
 /*
  * The whole path: O = restore(SparseAttn(reorder(Q,K,V), top-k(draft logits))).

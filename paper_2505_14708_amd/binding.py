@@ -24,8 +24,7 @@ DA_OK = 0
 
 EXPORTS = ["da_derive", "da_workspace_size", "da_build_perm", "da_draft_map", "da_select_blocks",
            "da_permute", "da_sparse_attn", "da_forward", "da_forward_ex", "da_global_sizes", "da_select_blocks_global",
-           "da_sparse_attn_lists", "da_forward_global", "da_status_string"]
-PROBE_EXPORTS = ["da_probe_mfma_bf16", "da_probe_copy", "da_probe_read"]      # include/da_probe.h
+           "da_sparse_attn_lists", "da_forward_global", "da_sparse_attn_ex", "da_wait_failures", "da_status_string"]
 
 
 class da_problem(ctypes.Structure):
@@ -81,12 +80,8 @@ def lib() -> ctypes.CDLL:
         L.da_select_blocks_global.argtypes = [P, V, V, V, V, V, ctypes.c_size_t, V]
         L.da_sparse_attn_lists.argtypes = [P, V, V, V, V, V, ctypes.c_int64, V, V, V]
         L.da_forward_global.argtypes = [P, V, V, V, V, V, V, V, ctypes.c_size_t, V]
-        L.da_probe_mfma_bf16.argtypes = [ctypes.c_int, V, ctypes.POINTER(ctypes.c_double), V]
-        L.da_probe_mfma_bf16.restype = ctypes.c_int
-        L.da_probe_copy.argtypes = [V, V, ctypes.c_size_t, V]
-        L.da_probe_copy.restype = ctypes.c_int
-        L.da_probe_read.argtypes = [V, ctypes.c_size_t, V, V]
-        L.da_probe_read.restype = ctypes.c_int
+        L.da_sparse_attn_ex.argtypes = [P, V, V, V, V, V, V, ctypes.c_int, V, V]
+        L.da_wait_failures.argtypes = [ctypes.POINTER(ctypes.c_uint64)]
         L.da_status_string.argtypes = [ctypes.c_int]
         L.da_status_string.restype = ctypes.c_char_p
         for name in EXPORTS[:-1]:
@@ -211,16 +206,13 @@ def da_forward_global(p, Q, K, V, O, ws, row_ptr_out=None, cols_out=None, stream
            "da_forward_global")
 
 
-def da_probe_mfma_bf16(iters: int, sink, stream=None) -> float:
-    """Enqueue the matrix-instruction loop; returns the flop one launch performs."""
-    flop = ctypes.c_double(0.0)
-    _check(lib().da_probe_mfma_bf16(int(iters), _ptr(sink), ctypes.byref(flop), _stream(stream)), "da_probe_mfma_bf16")
-    return float(flop.value)
+def da_sparse_attn_ex(p, Q, Kp, Vt, idx, O, lse=None, original_order=0, tile_counts=None, stream=None):
+    _check(lib().da_sparse_attn_ex(ctypes.byref(p), _ptr(Q), _ptr(Kp), _ptr(Vt), _ptr(idx), _ptr(O), _ptr(lse),
+                                   int(original_order), _ptr(tile_counts), _stream(stream)), "da_sparse_attn_ex")
 
 
-def da_probe_copy(src, dst, nbytes: int, stream=None):
-    _check(lib().da_probe_copy(_ptr(src), _ptr(dst), ctypes.c_size_t(int(nbytes)), _stream(stream)), "da_probe_copy")
-
-
-def da_probe_read(src, nbytes: int, sink, stream=None):
-    _check(lib().da_probe_read(_ptr(src), ctypes.c_size_t(int(nbytes)), _ptr(sink), _stream(stream)), "da_probe_read")
+def da_wait_failures() -> int:
+    """Waves of the bf16 attention kernel that gave up waiting for a tile (synchronises the device)."""
+    n = ctypes.c_uint64(0)
+    _check(lib().da_wait_failures(ctypes.byref(n)), "da_wait_failures")
+    return int(n.value)

@@ -194,9 +194,38 @@ int da_sparse_attn(const da_problem* p, const void* Qp, const void* Kp, const vo
     return DA_ERR_ALIGN;
   if (!attn_supported(q)) return DA_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
-  if (q.dtype == DA_BF16) return hip_status(launch_attn_bf16_ring(q, Qp, Kp, Vt, idx, nullptr, 0, Op, lse, false, s));
+  if (q.dtype == DA_BF16)
+    return hip_status(launch_attn_bf16_ring(q, Qp, Kp, Vt, idx, nullptr, 0, Op, lse, false, nullptr, s));
   return hip_status(
       launch_attn_f32(q, (const float*)Qp, (const float*)Kp, (const float*)Vt, idx, nullptr, 0, (float*)Op, lse, s));
+}
+
+int da_sparse_attn_ex(const da_problem* p, const void* Q, const void* Kp, const void* Vt, const int32_t* idx, void* O,
+                      float* lse, int original_order, uint64_t* tile_counts, void* stream) {
+  Geo q;
+  int st = check_problem(p, &q);
+  if (st != DA_OK) return st;
+  if (!Q || !Kp || !Vt || !idx || !O) return DA_ERR_NULL;
+  if (original_order != 0 && original_order != 1) return DA_ERR_DIM;
+  if (misaligned(Q) || misaligned(Kp) || misaligned(Vt) || misaligned(idx) || misaligned(O) || misaligned(lse) ||
+      ((uintptr_t)tile_counts & 7u) != 0)
+    return DA_ERR_ALIGN;
+  if (!attn_supported(q)) return DA_ERR_UNSUPPORTED;
+  if (q.dtype != DA_BF16) {
+    if (original_order || tile_counts) return DA_ERR_UNSUPPORTED;
+    return hip_status(launch_attn_f32(q, (const float*)Q, (const float*)Kp, (const float*)Vt, idx, nullptr, 0, (float*)O,
+                                      lse, (hipStream_t)stream));
+  }
+  return hip_status(launch_attn_bf16_ring(q, Q, Kp, Vt, idx, nullptr, 0, O, lse, original_order != 0,
+                                          (unsigned long long*)tile_counts, (hipStream_t)stream));
+}
+
+int da_wait_failures(uint64_t* count) {
+  if (!count) return DA_ERR_NULL;
+  unsigned long long c = 0ull;
+  if (read_wait_failures(&c) != hipSuccess) return DA_ERR_HIP;
+  *count = c;
+  return DA_OK;
 }
 
 // da_forward and da_forward_global: the same launches but for the selection
@@ -277,7 +306,7 @@ static int forward_impl(const da_problem* p, bool whole_map, const da_layout* in
   // Algorithm 1: reorder V (block-transposed; for bf16 as matrix operands)
   if ((e = launch_permute(q, V, vt, bf16 ? DA_REORDER_VOP : DA_REORDER_VT, s)) != hipSuccess) return DA_ERR_HIP;
   // SparseAttn
-  if (bf16) return hip_status(launch_attn_bf16_ring(q, Q, kp, vt, idx, row_ptr, cap, O, nullptr, true, s));
+  if (bf16) return hip_status(launch_attn_bf16_ring(q, Q, kp, vt, idx, row_ptr, cap, O, nullptr, true, nullptr, s));
   e = launch_attn_f32(q, (const float*)qp, (const float*)kp, (const float*)vt, idx, row_ptr, cap, (float*)op, nullptr, s);
   if (e != hipSuccess) return DA_ERR_HIP;
   // Algorithm 2: restore
@@ -334,7 +363,7 @@ int da_sparse_attn_lists(const da_problem* p, const void* Qp, const void* Kp, co
     return DA_ERR_ALIGN;
   if (!attn_supported(q, true)) return DA_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
-  if (q.dtype == DA_BF16) return hip_status(launch_attn_bf16_ring(q, Qp, Kp, Vt, cols, row_ptr, cap, Op, lse, false, s));
+  if (q.dtype == DA_BF16) return hip_status(launch_attn_bf16_ring(q, Qp, Kp, Vt, cols, row_ptr, cap, Op, lse, false, nullptr, s));
   return hip_status(launch_attn_f32(q, (const float*)Qp, (const float*)Kp, (const float*)Vt, cols, row_ptr, cap,
                                     (float*)Op, lse, s));
 }

@@ -98,7 +98,10 @@ hipError_t launch_select_global(const Geo& q, long long budget, long long cap, c
 // bf16 block-sparse attention (k_attn_bf16_ring.hip)
 int attn_bf16_ring_fits(const Geo& q, bool any_length = false);
 // direct: Qp and Op are Q and O in the original token order (lse stays in slot order)
+// tile_counts (may be NULL): two counters the waves add to: tiles gone through, tiles whose second product ran
 hipError_t launch_attn_bf16_ring(const Geo& q, const void* Qp, const void* Kp, const void* Vt, const int32_t* idx,
-                                 const int32_t* row_ptr, long long cap, void* Op, float* lse, bool direct, hipStream_t s);
+                                 const int32_t* row_ptr, long long cap, void* Op, float* lse, bool direct,
+                                 unsigned long long* tile_counts, hipStream_t s);
+hipError_t read_wait_failures(unsigned long long* count);
 
 }  // namespace da

@@ -85,6 +85,10 @@ constexpr float kLazy = 8.0f;                     // move the running max only p
 constexpr float kDropLog2 = 14.0f;                // all keys dropped from a row together weigh less than 2^-14 of its largest term
 constexpr int kSpinLimit = 1 << 20;
 
+// Waves whose bounded wait for a tile ran out since the library was loaded (their rows were written as NaN).
+// No valid input makes that happen; the host can ask (da_wait_failures).
+__device__ unsigned long long g_wait_failures = 0ull;
+
 // ---------------------------------------------------------------------------------- tile movement
 // 16 KB tile, rows of ROWB bytes, moved 1 KB (64 lanes x 16 B) per step; step `it` covers rows
 // it*RPS .. it*RPS+RPS-1 (RPS*ROWB = 1024), so global and LDS offsets are both it*1024 plus a
@@ -102,9 +106,15 @@ __device__ inline void tile_lane_offsets(int lane, unsigned loff[4]) {
   }
 }
 
-// Direct-to-LDS load of 16 bytes per lane: lane i's data lands at m0 + 16*i.
+// Direct-to-LDS load of 16 bytes per lane: lane i's data lands at m0 + 16*i.  m0 is put back afterwards (the
+// load has read it by then), so whatever the compiler keeps in it across this statement survives.
 __device__ __forceinline__ void dma16(const unsigned char* g, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory");
+  unsigned keep;
+  asm volatile(
+      "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+      : "=&s"(keep)
+      : "v"(g), "s"(lds_addr)
+      : "memory");
 }
 __device__ __forceinline__ void dma_tile(const unsigned char* src, unsigned lds_addr, const unsigned (&loff)[4]) {
 #pragma unroll
@@ -291,7 +301,8 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
                                                                const int32_t* __restrict__ idx,
                                                                const int32_t* __restrict__ row_ptr, long long cap,
                                                                unsigned char* __restrict__ Op, float* __restrict__ lse,
-                                                               int balance, float skip, int direct) {
+                                                               int balance, float skip, int direct,
+                                                               unsigned long long* __restrict__ tile_counts) {
   __shared__ __attribute__((aligned(1024))) unsigned char smem[LDS_TOTAL];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
@@ -646,6 +657,7 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
     pending = L;
   };
   bool gave_up = false;
+  int tiles_seen = 0, tiles_kept = 0;                 // (scalar registers; reported when the caller asks for the counts)
   int snap = look();
   // The walk, 64 entries at a time: lane i holds entry base + i, a ballot tells which of them
   // are mine.  Entries that are not mine cost nothing.
@@ -684,7 +696,9 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
         const unsigned char* kaddr[8];
 #pragma unroll
         for (int t = 0; t < 8; ++t) kaddr[t] = slot + kofs[t];
-        compute_tile(kaddr, Vlane + (long long)(e & 0x3fffffu) * V_TILE, hh, nv, pad_query, skip, qf, o, st);
+        const bool kept = compute_tile(kaddr, Vlane + (long long)(e & 0x3fffffu) * V_TILE, hh, nv, pad_query, skip, qf, o, st);
+        tiles_seen += 1;
+        tiles_kept += kept ? 1 : 0;
       }
       // my reads of the slot are complete: one reader less
       wait_lds();
@@ -695,6 +709,11 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
     }
   }
   publish();
+  if (tile_counts != nullptr && lane == 0 && tiles_seen) {
+    atomicAdd(&tile_counts[0], (unsigned long long)tiles_seen);
+    atomicAdd(&tile_counts[1], (unsigned long long)tiles_kept);
+  }
+  if (gave_up && lane == 0) atomicAdd(&g_wait_failures, 1ull);
   __syncthreads();                                    // everyone is done with the ring: reuse it to stage the output
   if (!live) {
     // 32 pad slots and nothing else: their rows of the reordered output are zeroed (in the original
@@ -756,7 +775,8 @@ int attn_bf16_ring_fits(const Geo& q, bool any_length) {
 }
 
 hipError_t launch_attn_bf16_ring(const Geo& q, const void* Qp, const void* Kp, const void* Vt, const int32_t* idx,
-                                 const int32_t* row_ptr, long long cap, void* Op, float* lse, bool direct, hipStream_t s) {
+                                 const int32_t* row_ptr, long long cap, void* Op, float* lse, bool direct,
+                                 unsigned long long* tile_counts, hipStream_t s) {
   const int per_frame = q.gh * q.gw;
   const int sub = q.block / ring::BS, fg = 4 / sub;
   const ring::TailPlan plan = ring::tail_plan(q, fg);
@@ -765,13 +785,20 @@ hipError_t launch_attn_bf16_ring(const Geo& q, const void* Qp, const void* Kp, c
   const float skip = log2f((float)q.k * (float)q.block) + ring::kDropLog2;
   auto go = [&](auto kernel) {
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(512), 0, s, q, (const unsigned char*)Qp, (const unsigned char*)Kp,
-                       (const unsigned char*)Vt, idx, row_ptr, cap, (unsigned char*)Op, lse, balance, skip, direct ? 1 : 0);
+                       (const unsigned char*)Vt, idx, row_ptr, cap, (unsigned char*)Op, lse, balance, skip, direct ? 1 : 0, tile_counts);
   };
   if (sub == 1 && !row_ptr) go(ring::attn_bf16_ring_kernel<1, false>);
   else if (sub == 1) go(ring::attn_bf16_ring_kernel<1, true>);
   else if (!row_ptr) go(ring::attn_bf16_ring_kernel<2, false>);
   else go(ring::attn_bf16_ring_kernel<2, true>);
   return hipGetLastError();
+}
+
+// Waves that gave up waiting for a tile since the library was loaded on the current device (synchronises).
+hipError_t read_wait_failures(unsigned long long* count) {
+  hipError_t e = hipDeviceSynchronize();
+  if (e != hipSuccess) return e;
+  return hipMemcpyFromSymbol(count, HIP_SYMBOL(ring::g_wait_failures), sizeof(*count), 0, hipMemcpyDeviceToHost);
 }
 
 }  // namespace da

@@ -80,14 +80,14 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(Geo q, const float* __rest
       }
     }
   }
-  float inv = 1.0f / l;
+  const float inv = l > 0.f ? 1.0f / l : 0.f;   // an empty list: zero rows
   float* orow = Op + (qb * 64 + lane) * D;
 #pragma unroll
   for (int c = 0; c < D; c += 4) {
     float4 t = make_float4(o[c] * inv, o[c + 1] * inv, o[c + 2] * inv, o[c + 3] * inv);
     *(float4*)(orow + c) = t;
   }
-  if (lse) lse[qb * 64 + lane] = m * (float)(1.0 / sqrt((double)D)) + logf(l);
+  if (lse) lse[qb * 64 + lane] = l > 0.f ? m * (float)(1.0 / sqrt((double)D)) + logf(l) : -INFINITY;
 }
 
 hipError_t launch_attn_f32(const Geo& q, const float* Qp, const float* Kp, const float* Vt, const int32_t* idx,

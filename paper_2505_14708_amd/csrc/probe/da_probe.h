@@ -1,7 +1,8 @@
 /*
  * da_probe.h - three measuring sticks for bench.py: what the machine in front of us actually
  * sustains, next to its published peaks.  For callers that report a fraction of roofline and
- * want the measured ceiling beside the nominal one; not part of the attention path.
+ * want the measured ceiling beside the nominal one; not part of the attention path and not in
+ * the product library: they are built into a library of their own (libdaprobe.so).
  */
 #ifndef DA_PROBE_H
 #define DA_PROBE_H
@@ -28,8 +29,9 @@ int da_probe_mfma_bf16(int iters, float* sink, double* flop, void* stream);
 int da_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
 
 /*
- * A plain read of `bytes` bytes (a multiple of 16; DEVICE pointer, 16-byte aligned) with 16-byte loads, eight in
- * flight per lane; what was read is folded into checksums in sink (DEVICE, at least 2^20 floats).  Only enqueues.
+ * A plain read of `bytes` bytes (a multiple of 16; DEVICE pointer, 16-byte aligned) with 16-byte loads, sixteen in
+ * flight per lane, 64 KB in a row per workgroup; what was read is folded into checksums in sink (DEVICE, at least
+ * 2^20 floats).  Only enqueues.
  */
 int da_probe_read(const void* src, size_t bytes, float* sink, void* stream);
 

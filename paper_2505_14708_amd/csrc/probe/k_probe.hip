@@ -50,22 +50,24 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const uint4* __restrict
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
 
-// a plain read: every lane keeps eight 16-byte loads in flight and folds what it read into one word
+// a plain read: a workgroup takes 64 KB in a row (sixteen 16-byte loads in flight per lane, each load of a wave one
+// contiguous KB), workgroups stride over the buffer; what was read is folded into one word per lane
 __global__ __launch_bounds__(256) void probe_read_kernel(const uint4* __restrict__ src, unsigned* __restrict__ sink, size_t n16) {
-  const size_t stride = (size_t)gridDim.x * 256;
-  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  constexpr size_t kPer = 256 * 16;                     // 16-byte pieces per workgroup and trip
   unsigned acc = 0u;
-  for (; i + 7 * stride < n16; i += 8 * stride) {
-    uint4 r[8];
+  size_t base = (size_t)blockIdx.x * kPer;
+  for (; base + kPer <= n16; base += (size_t)gridDim.x * kPer) {
+    uint4 r[16];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) r[t] = src[i + t * stride];
+    for (int t = 0; t < 16; ++t) r[t] = src[base + t * 256 + threadIdx.x];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) acc ^= r[t].x ^ r[t].y ^ r[t].z ^ r[t].w;
+    for (int t = 0; t < 16; ++t) acc ^= r[t].x ^ r[t].y ^ r[t].z ^ r[t].w;
   }
-  for (; i < n16; i += stride) {
-    const uint4 r = src[i];
-    acc ^= r.x ^ r.y ^ r.z ^ r.w;
-  }
+  if (base < n16)                                       // the last, partial stretch
+    for (size_t i = base + threadIdx.x; i < n16; i += 256) {
+      const uint4 r = src[i];
+      acc ^= r.x ^ r.y ^ r.z ^ r.w;
+    }
   sink[(blockIdx.x * 256u + threadIdx.x) & ((1u << 20) - 1u)] = acc;
 }
 

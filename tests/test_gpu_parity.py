@@ -373,6 +373,61 @@ def test_sparse_attn_deterministic(torch_mod, cases):
     assert torch.equal(O1.view(torch.int16), O2.view(torch.int16))
 
 
+def _expected_wave_tiles(ref, lists, block):
+    """Tiles the bf16 kernel's waves go through: a wave owns 32 query slots of a block and sits out when all of
+    them are pad slots; it takes one tile per 64-slot piece, holding a valid slot, of every kept key block."""
+    total = 0
+    for i, row in enumerate(lists):
+        waves = sum(1 for part in range(block // 32) if 32 * part < ref.valid[i])
+        tiles = sum(1 + (1 if ref.valid[j] > 64 else 0) for j in row)
+        total += waves * tiles
+    return total
+
+
+@pytest.mark.parametrize("name", ["bf16_480p_T3", "bf16_B2_T5", "bf16_8x16_ragged"])
+def test_sparse_attn_ex_original_order_and_tile_counts(torch_mod, cases, name):
+    """da_sparse_attn_ex: with original_order = 1 it reads Q and writes O where da_forward does and gives da_forward's
+    bits; its tile counts are the number of tiles the lists imply, and with scores all alike (Q scaled down: nothing
+    is negligible) every tile is carried out."""
+    torch = torch_mod
+    w, Q, K, V, refs = cases[name]
+    say(f"sparse_attn_ex {name}")
+    p = da.problem_of(w)
+    dims = da.da_derive(p)
+    dQ, dK, dV = (to_dev(x, w.dtype) for x in (Q, K, V))
+    ws = torch.empty(da.da_workspace_size(p), dtype=torch.uint8, device="cuda")
+    O1 = empty((w.B, w.H, dims.n, w.d), w.dtype)
+    idx = torch.empty((w.B, w.H, dims.g, dims.k), dtype=torch.int32, device="cuda")
+    da.da_forward(p, dQ, dK, dV, O1, ws, idx)
+    Kp = empty((w.B, w.H, dims.n_pad, w.d), w.dtype)
+    Vt = empty((w.B, w.H, dims.g, w.d, dims.block), w.dtype)
+    da.da_permute(p, dK, Kp, da.DA_REORDER_ROWS)
+    da.da_permute(p, dV, Vt, da.DA_REORDER_VOP)
+    O2 = empty((w.B, w.H, dims.n, w.d), w.dtype)
+    O2.fill_(float("nan"))
+    counts = torch.zeros(2, dtype=torch.int64, device="cuda")
+    da.da_sparse_attn_ex(p, dQ, Kp, Vt, idx, O2, None, 1, counts)
+    torch.cuda.synchronize()
+    assert torch.equal(O1.view(torch.int16), O2.view(torch.int16))
+    hidx = idx.cpu().numpy()
+    want = sum(_expected_wave_tiles(ref, hidx[b, h], dims.block) for (b, h), ref in refs.items())
+    seen, kept = (int(x) for x in counts.cpu().numpy())
+    say(f"  {name}: {seen} tiles gone through, {kept} carried out")
+    assert seen == want and 0 < kept <= seen
+    # scores all alike: every tile is carried out; the counters add up over calls
+    Qs = to_dev(W.to_storage(W.storage_to_f64(Q, w.dtype) * 2.0 ** -6, w.dtype), w.dtype)
+    da.da_sparse_attn_ex(p, Qs, Kp, Vt, idx, O2, None, 1, counts)
+    torch.cuda.synchronize()
+    seen2, kept2 = (int(x) for x in counts.cpu().numpy())
+    assert seen2 == 2 * want and kept2 - kept == want
+    got = to_host_f64(O2, w.dtype)
+    for (b, h), ref in refs.items():
+        qp = oa.permute(oa.widen_f64(Q[b, h], w.dtype) * 2.0 ** -6, ref.perm)
+        ref_o = oa.sparse_attention_blocks(qp, ref.permuted64("k"), ref.permuted64("v"), hidx[b, h], ref.valid, dims.block)
+        emax, emean = output_error(got[b, h], oa.restore(ref_o, ref.inv))
+        assert emax <= 2e-2 and emean <= 2e-3, (emax, emean)
+
+
 # ----------------------------------------------------------------------------- whole path
 @pytest.mark.parametrize("name", _names())
 def test_forward_end_to_end(torch_mod, cases, name):

@@ -148,12 +148,14 @@ def test_sparse_attn_lists_stage(torch_mod, cases, name):
         assert lerr < (2e-2 if w.dtype == W.BF16 else 1e-4)
 
 
-def test_sparse_attn_lists_empty_and_unsorted_rows(torch_mod, cases):
-    """Lists a caller made by hand: some query blocks attend nothing (their rows come out as zeros), the others hold
-    their blocks in any order."""
+@pytest.mark.parametrize("name", ["bf16_B2_T5", "f32_ragged"])
+def test_sparse_attn_lists_empty_and_unsorted_rows(torch_mod, cases, name):
+    """Lists a caller made by hand: some query blocks attend nothing (their rows come out as zeros, in both storage
+    types), the others hold their blocks in any order.  The tolerance is the stated one, on every head's output as a
+    whole and, the maximum, on every block."""
     torch = torch_mod
-    w, Q, K, V, refs = cases["bf16_B2_T5"]
-    say("sparse_attn_lists with empty rows")
+    w, Q, K, V, refs = cases[name]
+    say(f"sparse_attn_lists with empty rows, {name}")
     p = da.problem_of(w)
     dims = da.da_derive(p)
     g = dims.g
@@ -162,7 +164,7 @@ def test_sparse_attn_lists_empty_and_unsorted_rows(torch_mod, cases):
     for key in refs:
         rows = []
         for i in range(g):
-            n = 0 if i % 7 == 3 else int(rng.integers(1, 12))
+            n = 0 if i % 7 == 3 else int(rng.integers(1, min(12, g + 1)))
             rows.append(rng.choice(g, size=n, replace=False).astype(np.int64))
         lists[key] = rows
     cap = (max(sum(len(r) for r in rows) for rows in lists.values()) + 3) // 4 * 4
@@ -177,19 +179,27 @@ def test_sparse_attn_lists_empty_and_unsorted_rows(torch_mod, cases):
     da.da_permute(p, to_dev(V, w.dtype), Vt, da.v_layout(w.dtype))
     Op = empty((w.B, w.H, dims.n_pad, w.d), w.dtype)
     Op.fill_(7.0)
-    da.da_sparse_attn_lists(p, Qp, Kp, Vt, row_ptr, cols, cap, Op, None)
+    lse = torch.empty((w.B, w.H, dims.n_pad), dtype=torch.float32, device="cuda")
+    da.da_sparse_attn_lists(p, Qp, Kp, Vt, row_ptr, cols, cap, Op, lse)
     torch.cuda.synchronize()
+    assert bool(torch.isfinite(Op.float()).all())
     got = to_host_f64(Op, w.dtype)
+    tol_max, tol_mean = TOL[w.dtype]
     for (b, h), ref in refs.items():
         full = [i for i in range(g) if len(lists[(b, h)][i])]
         want = ref.attention(rows=full, idx=lists[(b, h)])
+        live = np.zeros(dims.n_pad, bool)
         for i in range(g):
             sl = slice(i * dims.block, i * dims.block + ref.valid[i])
             if len(lists[(b, h)][i]) == 0:
                 assert (got[b, h][sl] == 0.0).all(), i
             else:
-                emax, emean = output_error(got[b, h][sl], want[sl])
-                assert emax <= 2e-2 and emean <= 2.5e-3, (i, emax, emean)
+                live[sl] = True
+                emax, _ = output_error(got[b, h][sl], want[sl])
+                assert emax <= tol_max, (i, emax)
+        emax, emean = output_error(got[b, h][live], want[live])
+        say(f"  {name} head {(b, h)}: max-abs {emax:.3e} mean-abs {emean:.3e}")
+        assert emean <= tol_mean, emean
 
 
 def test_sparse_attn_lists_equals_fixed_k(torch_mod, cases):

@@ -17,16 +17,35 @@ pytestmark = pytest.mark.skipif(not os.path.exists(da.LIB_PATH), reason="library
 FAKE = 0x10000  # a non-NULL, 16-byte aligned value that is never dereferenced on the error paths
 
 
+def _exported(path):
+    """Dynamic symbols a shared library defines."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", path], capture_output=True, text=True, check=True).stdout
+    return {line.split()[-1] for line in out.splitlines() if line.strip()}
+
+
 def test_every_declared_symbol_is_exported():
+    """include/ holds da.h alone; the product library exports what it declares, and none of the bench's
+    measuring sticks (they live in a library of their own)."""
     header = open(os.path.join(ROOT, "include", "da.h")).read()
     declared = set(re.findall(r"\b(da_[a-z0-9_]+)\s*\(", header))
     assert declared == set(da.EXPORTS)
-    probes = set(re.findall(r"\b(da_[a-z0-9_]+)\s*\(", open(os.path.join(ROOT, "include", "da_probe.h")).read()))
-    assert probes == set(da.PROBE_EXPORTS)
-    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["da.h", "da_probe.h"]
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["da.h"]
     L = da.lib()
-    for name in declared | probes:
+    for name in declared:
         assert getattr(L, name) is not None
+    c_names = {n for n in _exported(da.LIB_PATH) if n.startswith("da_")}
+    assert c_names == declared, c_names ^ declared
+
+
+def test_probe_library_is_separate():
+    from paper_2505_14708_amd import probe
+    if not os.path.exists(probe.LIB_PATH):
+        pytest.skip("probe library not built")
+    header = open(os.path.join(ROOT, "paper_2505_14708_amd", "csrc", "probe", "da_probe.h")).read()
+    declared = set(re.findall(r"\b(da_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(probe.EXPORTS)
+    assert {n for n in _exported(probe.LIB_PATH) if n.startswith("da_")} == declared
 
 
 def test_struct_layout_matches_header():
@@ -86,6 +105,14 @@ def test_null_alignment_mode_and_support_checks():
               da.problem(1, 1, 2, 16, 16, 64, ph=8, pw=16, dtype=da.DA_F32),
               da.problem(1, 1, 2, 16, 16, 64, dtype=da.DA_BF16), da.problem(1, 1, 2, 16, 16, 256, dtype=da.DA_F32)):
         assert _status(da.da_sparse_attn, q, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0) == -3
+    # da_sparse_attn_ex: the same checks, plus its two extras
+    assert _status(da.da_sparse_attn_ex, p, FAKE, FAKE, FAKE, None, FAKE, None, 0, None, 0) == -1
+    assert _status(da.da_sparse_attn_ex, p, FAKE, FAKE, FAKE, FAKE, FAKE, None, 2, None, 0) == -2
+    assert _status(da.da_sparse_attn_ex, p, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0, FAKE + 4, 0) == -5
+    f = da.problem_of(W.CONFIGS["tiny_fp32"])
+    assert _status(da.da_sparse_attn_ex, f, FAKE, FAKE, FAKE, FAKE, FAKE, None, 1, None, 0) == -3   # f32: no in-place order
+    assert _status(da.da_sparse_attn_ex, f, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0, FAKE, 0) == -3   # f32: no tile counts
+    assert da.lib().da_wait_failures(None) == -1
     # bf16 attention keeps per-workgroup block lists in LDS: more than ~7000 blocks with nothing dropped do not fit
     q = da.problem(1, 1, 8000, 8, 8, 128)
     assert _status(da.da_sparse_attn, q, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0) == -3
