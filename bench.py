@@ -7,12 +7,23 @@ workload is the headline configuration: 118 800 tokens (33 latent frames of 45x8
 heads of 128, 8x8 pooling, 90 % sparsity, bf16.  Prints ONE JSON line.
 
   value        effective TFLOP/s of the whole step: 4*N*N*d*H*(k/g) / step time
-  ms_per_step  milliseconds per layer (the other half of the metric)
-  roofline     the block-sparse attention kernel against the bf16 MFMA peak; its launch
-               duration is measured with HIP events on the launch stream in a second loop
-               that issues the C-ABI stages one by one (da_forward fuses some of them: it
-               reorders K inside the pooling pass and makes no reordered copies of Q and O,
-               so ms_per_step is smaller than the sum of stages_ms)
+  ms_per_step  milliseconds per layer (the other half of the metric): the K timed steps / K;
+               ms_per_step_median is the median of the same K steps (HIP events between them)
+  roofline     the block-sparse attention kernel against the bf16 MFMA peak, three ways, all
+               measured in this run with HIP events on the launch stream (medians over the steps):
+                 frac           EFFECTIVE flop 4*N*N*d*H*(k/g) / launch time / peak, for the launch
+                                da_forward makes (queries read, outputs written in the original
+                                token order): the figure the build target names;
+                 executed.frac  flop of the matrix instructions the kernel actually issued (it counts
+                                its tiles: da_sparse_attn_ex) / the same time / peak.  Padding adds
+                                work, the kernel's drop rule takes work away; on these peaked
+                                synthetic inputs it takes away a lot;
+                 no_drop.frac   the same launch, same block lists, with Q scaled by 2^-5 so that the
+                                scores of a row lie close together and nothing is dropped: what the
+                                kernel does on inputs whose attention is not peaked.
+               The other stages are timed in a loop that issues the C-ABI calls one by one
+               (da_forward fuses some of them: it reorders K inside the pooling pass and makes
+               no reordered copies of Q and O, so ms_per_step is smaller than their sum)
   cpu_baseline the NumPy float64 oracle timed on this host on a bounded sample
 """
 from __future__ import annotations
@@ -34,10 +45,12 @@ from paper_2505_14708_amd import workloads as W  # noqa: E402
 METRIC = "sparse-attn ms/layer + effective MFMA TFLOP/s @118.8k tokens, 90% sparsity"
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
-# HBM-side bytes per launch of the attention kernel (read, written), from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs of this program, scaled by what the same counters read for the row-copy kernel of known
-# size in the same run (profiles/pmc_traffic_720p_hunyuan.txt).  Workloads without a counter run: null.
-ATTN_TRAFFIC_BYTES = {"720p_hunyuan": (56.36e9, 0.754e9)}
+# HBM-side bytes per launch of the attention kernel (read, written): NOT measured in this run (counters need
+# rocprofv3) but copied from a counter run of this program: FETCH_SIZE and WRITE_SIZE, scaled by what the same
+# counters read for the row-copy kernel of known size in the same run.  The file named holds the figures and the
+# command; it is regenerated whenever the kernel changes.  Workloads without a counter run: null.
+ATTN_TRAFFIC = {"720p_hunyuan": {"read": 56.36e9, "written": 0.754e9, "source": "profiles/pmc_traffic_720p_hunyuan.txt"}}
+FLOP_PER_MFMA = 2.0 * 32 * 32 * 16     # v_mfma_f32_32x32x16_bf16
 
 
 def cpu_baseline(w, Q, K, V, budget_s=20.0, whole_map=False):
@@ -89,13 +102,14 @@ def cpu_baseline(w, Q, K, V, budget_s=20.0, whole_map=False):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="720p_hunyuan", choices=list(W.CONFIGS) + list(W.EXTRA_CONFIGS))
     ap.add_argument("--selection", default="rows", choices=["rows", "whole_map"],
                     help="rows: k key blocks per query block (the headline); whole_map: the threshold over a head's "
                          "whole map (Section 3.2.2), lists of any length")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-probes", action="store_true", help="skip the machine's measuring sticks")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path is independent per head and would shard "
@@ -111,12 +125,25 @@ def main():
     from paper_2505_14708_amd import binding as da
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    tdt = torch.float32 if w.dtype == W.F32 else torch.bfloat16
+    bf16 = w.dtype == W.BF16
+    tdt = torch.bfloat16 if bf16 else torch.float32
 
     def dev(x):
-        if w.dtype == W.F32:
+        if not bf16:
             return torch.from_numpy(x).cuda()
         return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+
+    def timed(fn, reps):
+        """Durations in ms of `reps` calls of fn, one HIP event pair each, on the launch stream."""
+        out = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            torch.cuda.synchronize()
+            out.append(a.elapsed_time(b))
+        return out
 
     p = da.problem_of(w)
     dims = da.da_derive(p)
@@ -137,23 +164,23 @@ def main():
         else:
             da.da_forward(p, dQ, dK, dV, O, ws)
 
-    # ---- the timed region: K steps of the whole path
+    # ---- the timed region: K steps of the whole path, events between the steps for the median
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(args.steps):
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    marks[0].record()
+    for i in range(args.steps):
         step()
-    e1.record()
+        marks[i + 1].record()
     torch.cuda.synchronize()
-    ms_step = e0.elapsed_time(e1) / args.steps
+    ms_step = marks[0].elapsed_time(marks[-1]) / args.steps
+    ms_step_median = float(np.median([marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)]))
 
     # ---- the same launches stage by stage, HIP events (torch's current stream is the launch stream)
-    es = torch.float32 if w.dtype == W.F32 else torch.bfloat16
-    Qp = torch.empty((w.B, w.H, dims.n_pad, w.d), dtype=es, device="cuda")
+    Qp = torch.empty((w.B, w.H, dims.n_pad, w.d), dtype=tdt, device="cuda")
     Kp, Op = torch.empty_like(Qp), torch.empty_like(Qp)
-    Vt = torch.empty((w.B, w.H, g, w.d, dims.block), dtype=es, device="cuda")
+    Vt = torch.empty((w.B, w.H, g, w.d, dims.block), dtype=tdt, device="cuda")
     q_pool = torch.empty((w.B, w.H, g, w.d), dtype=torch.float32, device="cuda")
     k_pool = torch.empty_like(q_pool)
     logits = torch.empty((w.B, w.H, g, g), dtype=torch.float32, device="cuda")
@@ -171,10 +198,10 @@ def main():
         ("select", select),
         ("reorder_qkv", lambda: (da.da_permute(p, dQ, Qp, da.DA_REORDER_ROWS), da.da_permute(p, dK, Kp, da.DA_REORDER_ROWS),
                                  da.da_permute(p, dV, Vt, da.v_layout(p.dtype)))),
-        ("sparse_attn", attend),
+        ("sparse_attn_reordered_q", attend),
         ("restore", lambda: da.da_permute(p, Op, O, da.DA_RESTORE)),
     ]
-    acc = {name: 0.0 for name, _ in stages}
+    per = {name: [] for name, _ in stages}
     for it in range(args.warmup + args.steps):
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)]
         evs[0].record()
@@ -184,71 +211,102 @@ def main():
         torch.cuda.synchronize()
         if it >= args.warmup:
             for i, (name, _) in enumerate(stages):
-                acc[name] += evs[i].elapsed_time(evs[i + 1])
-    stage_ms = {name: v / args.steps for name, v in acc.items()}
-    attn_ms = stage_ms["sparse_attn"]
-    esz = 4 if w.dtype == W.F32 else 2
+                per[name].append(evs[i].elapsed_time(evs[i + 1]))
+    stage_ms = {name: float(np.median(v)) for name, v in per.items()}
+    esz = 2 if bf16 else 4
     reorder_bytes = 3.0 * (dims.n + dims.n_pad) * w.d * esz * w.B * w.H
     restore_bytes = 1.0 * (dims.n + dims.n_pad) * w.d * esz * w.B * w.H
 
-    # ---- what this machine sustains: a pure matrix-instruction loop (~10 ms of it) and a plain copy
-    sink = torch.empty(1 << 20, dtype=torch.float32, device="cuda")
-    da.da_probe_mfma_bf16(2000, sink)                      # warm-up
-    torch.cuda.synchronize()
-    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    pe[0].record()
-    probe_flop = da.da_probe_mfma_bf16(6000, sink)
-    pe[1].record()
-    torch.cuda.synchronize()
-    mfma_measured = probe_flop / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e12
-    csrc, cdst = dQ.view(torch.uint8).flatten(), torch.empty(dQ.numel() * dQ.element_size(), dtype=torch.uint8, device="cuda")
-    da.da_probe_copy(csrc, cdst, csrc.numel())
-    torch.cuda.synchronize()
-    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    pe[0].record()
-    for _ in range(4):
-        da.da_probe_copy(csrc, cdst, csrc.numel())
-    pe[1].record()
-    torch.cuda.synchronize()
-    copy_measured = 4 * 2.0 * csrc.numel() / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9
-    # a plain read of Q and K one after the other (more than the last-level cache holds)
-    ksrc = dK.view(torch.uint8).flatten()
-    da.da_probe_read(csrc, csrc.numel(), sink)
-    torch.cuda.synchronize()
-    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    pe[0].record()
-    for _ in range(2):
-        da.da_probe_read(csrc, csrc.numel(), sink)
-        da.da_probe_read(ksrc, ksrc.numel(), sink)
-    pe[1].record()
-    torch.cuda.synchronize()
-    read_measured = 2 * (csrc.numel() + ksrc.numel()) / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e9
-    del cdst, sink
+    # ---- the attention launch da_forward makes (bf16, k per row: Q and O in the original token order), timed by
+    # itself; the tiles it goes through and carries out; and the same launch with nothing dropped
+    roof = {"kernel": "da::ring::attn_bf16_ring_kernel", "bound": "mfma", "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+            "flop_per_launch": eff_flop, "timing": f"median of {args.steps} launches, HIP events on the launch stream"}
+    if bf16 and not whole_map:
+        counts = torch.zeros(2, dtype=torch.int64, device="cuda")
+
+        def tile_flop(q_in):
+            counts.zero_()
+            da.da_sparse_attn_ex(p, q_in, Kp, Vt, idx, O, None, 1, counts)
+            torch.cuda.synchronize()
+            seen, kept = (int(x) for x in counts.cpu().numpy())
+            return seen, kept, 16.0 * (seen + kept) * FLOP_PER_MFMA
+
+        direct = lambda: da.da_sparse_attn_ex(p, dQ, Kp, Vt, idx, O, None, 1, None)
+        timed(direct, args.warmup)
+        attn_ms = float(np.median(timed(direct, args.steps)))
+        seen, kept, exe_flop = tile_flop(dQ)
+        roof.update({"launch": "da_sparse_attn_ex, original_order=1: the launch da_forward makes",
+                     "launch_ms": attn_ms, "achieved": eff_flop / (attn_ms * 1e-3) / 1e12,
+                     "frac": eff_flop / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                     "executed": {"tiles": seen, "tiles_carried_out": kept, "flop_per_launch": exe_flop,
+                                  "achieved": exe_flop / (attn_ms * 1e-3) / 1e12,
+                                  "frac": exe_flop / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}})
+        dQs = dQ * (2.0 ** -5)                         # exact in bf16
+        flat = lambda: da.da_sparse_attn_ex(p, dQs, Kp, Vt, idx, O, None, 1, None)
+        timed(flat, 1)
+        flat_ms = float(np.median(timed(flat, max(5, args.steps // 2))))
+        seen2, kept2, exe2 = tile_flop(dQs)
+        roof["no_drop"] = {"what": "same launch and block lists, Q scaled by 2^-5: every tile is carried out",
+                           "launch_ms": flat_ms, "tiles": seen2, "tiles_carried_out": kept2,
+                           "achieved": eff_flop / (flat_ms * 1e-3) / 1e12,
+                           "frac": eff_flop / (flat_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                           "executed_frac": exe2 / (flat_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+        del dQs
+    else:
+        attn_ms = stage_ms["sparse_attn_reordered_q"]
+        roof.update({"launch": "the attention stage of the staged loop", "launch_ms": attn_ms,
+                     "achieved": eff_flop / (attn_ms * 1e-3) / 1e12,
+                     "frac": eff_flop / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS})
+    tr = ATTN_TRAFFIC.get(w.name) if not whole_map else None
+    roof["traffic"] = tr["read"] + tr["written"] if tr else None
+    roof["traffic_unit"] = "HBM-side bytes per launch (read + written)"
+    roof["traffic_source"] = (tr["source"] + " (a counter run of this program; not measured in this run)") if tr else None
+    roof["compulsory_bytes"] = 4.0 * dims.n_pad * w.d * esz * w.B * w.H
+
+    # ---- what this machine sustains: a pure matrix-instruction loop (~10 ms of it), a plain copy, a plain read
+    hbm = {"reorder_qkv_GBs": reorder_bytes / (stage_ms["reorder_qkv"] * 1e-3) / 1e9,
+           "restore_GBs": restore_bytes / (stage_ms["restore"] * 1e-3) / 1e9, "peak_GBs": PEAK_HBM_GBS}
+    if not args.no_probes:
+        from paper_2505_14708_amd import probe
+        sink = torch.empty(1 << 20, dtype=torch.float32, device="cuda")
+        probe.da_probe_mfma_bf16(2000, sink)               # warm-up
+        torch.cuda.synchronize()
+        flop = [0.0]
+        ms = timed(lambda: flop.__setitem__(0, probe.da_probe_mfma_bf16(6000, sink)), 1)[0]
+        roof["measured_mfma_loop"] = flop[0] / (ms * 1e-3) / 1e12
+        roof["frac_of_measured"] = roof["achieved"] / roof["measured_mfma_loop"]
+        csrc = dQ.view(torch.uint8).flatten()
+        ksrc = dK.view(torch.uint8).flatten()
+        cdst = torch.empty_like(csrc)
+        copy = lambda: probe.da_probe_copy(csrc, cdst, csrc.numel())
+        timed(copy, 1)
+        hbm["measured_copy_GBs"] = 2.0 * csrc.numel() / (float(np.median(timed(copy, 5))) * 1e-3) / 1e9
+        # a plain read of Q and K one after the other (more than the last-level cache holds)
+        read = lambda: (probe.da_probe_read(csrc, csrc.numel(), sink), probe.da_probe_read(ksrc, ksrc.numel(), sink))
+        timed(read, 1)
+        hbm["measured_read_GBs"] = (csrc.numel() + ksrc.numel()) / (float(np.median(timed(read, 5))) * 1e-3) / 1e9
+        del cdst, sink
+    # the pooling pass by itself (Definition 3.2): Q and K read once, the pooled rows written
+    pool_only = lambda: da.da_draft_map(p, dQ, dK, q_pool, k_pool, None, None)
+    timed(pool_only, 1)
+    stage_ms["pool_only"] = float(np.median(timed(pool_only, max(5, args.steps // 2))))
+    pool_bytes = 2.0 * dims.n * w.d * esz * w.B * w.H + 2.0 * g * w.d * 4 * w.B * w.H
+    hbm["pool_GBs"] = pool_bytes / (stage_ms["pool_only"] * 1e-3) / 1e9
 
     out = {
         "metric": METRIC,
         "value": eff_flop / (ms_step * 1e-3) / 1e12,
         "unit": "TFLOP/s effective (whole step)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_step,
+        "ms_per_step": ms_step, "ms_per_step_median": ms_step_median,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if w.dtype == W.F32 else "bf16", "data": "synthetic",
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "d": w.d, "T": w.T, "frame": [w.fh, w.fw], "N": w.N,
                    "pool": [w.ph, w.pw], "sparsity": w.sparsity, "g": g, "k": k, "n_pad": int(dims.n_pad),
                    "selection": args.selection},
-        "roofline": {"kernel": "da::ring::attn_bf16_ring_kernel (da_sparse_attn)", "bound": "mfma",
-                     "achieved": eff_flop / (attn_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": eff_flop / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-                     "traffic": (sum(ATTN_TRAFFIC_BYTES[w.name]) if w.name in ATTN_TRAFFIC_BYTES and not whole_map
-                                 else None),
-                     "traffic_unit": "bytes per launch (read + written)",
-                     "launch_ms": attn_ms, "flop_per_launch": eff_flop,
-                     "measured_mfma_loop": mfma_measured,
-                     "frac_of_measured": eff_flop / (attn_ms * 1e-3) / 1e12 / mfma_measured},
+        "roofline": roof,
         "stages_ms": stage_ms,
-        "hbm_stages": {"reorder_qkv_GBs": reorder_bytes / (stage_ms["reorder_qkv"] * 1e-3) / 1e9,
-                       "restore_GBs": restore_bytes / (stage_ms["restore"] * 1e-3) / 1e9, "peak_GBs": PEAK_HBM_GBS,
-                       "measured_copy_GBs": copy_measured, "measured_read_GBs": read_measured},
+        "hbm_stages": hbm,
     }
     if whole_map:
         torch.cuda.synchronize()
