@@ -53,7 +53,8 @@ typedef enum da_status {
   DA_ERR_UNSUPPORTED = -3, /* valid, but no kernel: see da_sparse_attn */
   DA_ERR_WORKSPACE = -4,   /* ws_bytes is smaller than da_workspace_size() */
   DA_ERR_ALIGN = -5,       /* a device pointer is not 16-byte aligned */
-  DA_ERR_HIP = -6          /* the HIP runtime refused a launch */
+  DA_ERR_HIP = -6,         /* the HIP runtime refused a launch */
+  DA_ERR_SCRATCH = -7      /* the problem needs more scratch than the library's built-in buffer holds */
 } da_status;
 
 /* The problem statement of Definitions 3.1/3.2 and the inputs of Algorithm 1 (host struct). */
@@ -242,6 +243,19 @@ int da_global_sizes(const da_problem* p, da_global_dims* out /* host */);
  */
 int da_select_blocks_global(const da_problem* p, const float* scores, int32_t* row_ptr, int32_t* cols, uint8_t* mask,
                             void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * da_select_blocks_global for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments and result, minus ws: the scratch is a buffer of
+ * DA_STATIC_SCRATCH_BYTES bytes built into the library (one per device, held until the process ends; its address
+ * is looked up on the first call on a device).  The call allocates nothing and records no memset: everything that
+ * must start at zero is cleared by a fill kernel on `stream`.  A problem whose da_global_dims.select_ws exceeds
+ * DA_STATIC_SCRATCH_BYTES returns DA_ERR_SCRATCH and launches nothing.  All calls on one device share the one
+ * buffer: calls that may overlap on a device (different streams, different threads) race; order them.
+ */
+#define DA_STATIC_SCRATCH_BYTES (32u << 20)
+int da_select_blocks_global_static(const da_problem* p, const float* scores, int32_t* row_ptr, int32_t* cols,
+                                   uint8_t* mask, void* stream);
 
 /*
  * da_sparse_attn for lists of any length: query block i of head (b,h) attends the key blocks

@@ -21,10 +21,12 @@ def v_layout(dtype: int) -> int:
     return DA_REORDER_VOP if dtype == DA_BF16 else DA_REORDER_VT
 DA_POOL_AVG, DA_POOL_MAX = 0, 1
 DA_OK = 0
+DA_STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = ["da_derive", "da_workspace_size", "da_build_perm", "da_draft_map", "da_select_blocks",
            "da_permute", "da_sparse_attn", "da_forward", "da_forward_ex", "da_global_sizes", "da_select_blocks_global",
-           "da_sparse_attn_lists", "da_forward_global", "da_sparse_attn_ex", "da_wait_failures", "da_status_string"]
+           "da_sparse_attn_lists", "da_forward_global", "da_sparse_attn_ex", "da_wait_failures",
+           "da_select_blocks_global_static", "da_status_string"]
 
 
 class da_problem(ctypes.Structure):
@@ -78,6 +80,7 @@ def lib() -> ctypes.CDLL:
                                     ctypes.c_size_t, V]
         L.da_global_sizes.argtypes = [P, ctypes.POINTER(da_global_dims)]
         L.da_select_blocks_global.argtypes = [P, V, V, V, V, V, ctypes.c_size_t, V]
+        L.da_select_blocks_global_static.argtypes = [P, V, V, V, V, V]
         L.da_sparse_attn_lists.argtypes = [P, V, V, V, V, V, ctypes.c_int64, V, V, V]
         L.da_forward_global.argtypes = [P, V, V, V, V, V, V, V, ctypes.c_size_t, V]
         L.da_sparse_attn_ex.argtypes = [P, V, V, V, V, V, V, ctypes.c_int, V, V]
@@ -191,6 +194,11 @@ def da_select_blocks_global(p, scores, row_ptr, cols, ws, mask=None, stream=None
     nbytes = ws.numel() * ws.element_size()
     _check(lib().da_select_blocks_global(ctypes.byref(p), _ptr(scores), _ptr(row_ptr), _ptr(cols), _ptr(mask), _ptr(ws),
                                          ctypes.c_size_t(nbytes), _stream(stream)), "da_select_blocks_global")
+
+
+def da_select_blocks_global_static(p, scores, row_ptr, cols, mask=None, stream=None):
+    _check(lib().da_select_blocks_global_static(ctypes.byref(p), _ptr(scores), _ptr(row_ptr), _ptr(cols), _ptr(mask),
+                                                _stream(stream)), "da_select_blocks_global_static")
 
 
 def da_sparse_attn_lists(p, Qp, Kp, Vt, row_ptr, cols, cap, Op, lse=None, stream=None):

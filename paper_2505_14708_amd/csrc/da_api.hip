@@ -351,6 +351,21 @@ int da_select_blocks_global(const da_problem* p, const float* scores, int32_t* r
   return hip_status(launch_select_global(q, budget, cap, scores, row_ptr, cols, mask, ws, (hipStream_t)stream));
 }
 
+int da_select_blocks_global_static(const da_problem* p, const float* scores, int32_t* row_ptr, int32_t* cols,
+                                   uint8_t* mask, void* stream) {
+  Geo q;
+  int st = check_problem(p, &q);
+  if (st != DA_OK) return st;
+  if (!scores || !row_ptr || !cols) return DA_ERR_NULL;
+  if (misaligned(scores) || misaligned(row_ptr) || misaligned(cols) || misaligned(mask)) return DA_ERR_ALIGN;
+  long long budget, cap;
+  if (!global_budget(p, q, &budget, &cap)) return DA_ERR_DIM;
+  if (align_up(select_global_workspace(q)) > (size_t)DA_STATIC_SCRATCH_BYTES) return DA_ERR_SCRATCH;
+  void* ws = nullptr;
+  if (static_scratch(&ws) != hipSuccess) return DA_ERR_HIP;
+  return hip_status(launch_select_global(q, budget, cap, scores, row_ptr, cols, mask, ws, (hipStream_t)stream));
+}
+
 int da_sparse_attn_lists(const da_problem* p, const void* Qp, const void* Kp, const void* Vt, const int32_t* row_ptr,
                          const int32_t* cols, int64_t cap, void* Op, float* lse, void* stream) {
   Geo q;
@@ -382,6 +397,7 @@ const char* da_status_string(int status) {
     case DA_ERR_WORKSPACE: return "workspace too small";
     case DA_ERR_ALIGN: return "device pointer not aligned";
     case DA_ERR_HIP: return "HIP launch failed";
+    case DA_ERR_SCRATCH: return "the problem needs more scratch than the built-in buffer holds";
     default: return "unknown status";
   }
 }

@@ -93,6 +93,8 @@ hipError_t launch_attn_f32(const Geo& q, const float* Qp, const float* Kp, const
                            const int32_t* row_ptr, long long cap, float* Op, float* lse, hipStream_t s);
 // whole-map threshold selection (k_select_global.hip)
 size_t select_global_workspace(const Geo& q);
+// device address, on the current device, of the library's built-in scratch (DA_STATIC_SCRATCH_BYTES bytes)
+hipError_t static_scratch(void** ptr);
 hipError_t launch_select_global(const Geo& q, long long budget, long long cap, const float* scores, int32_t* row_ptr,
                                 int32_t* cols, uint8_t* mask, void* ws, hipStream_t s);
 // bf16 block-sparse attention (k_attn_bf16_ring.hip)

@@ -8,7 +8,13 @@
 // per head turns the counts into the row offsets (keys equal to the threshold are taken in row-major order
 // until the budget is used up; a row left empty keeps its best column), and every row writes its kept
 // columns in ascending order with an ordered ballot compaction.  Exact and deterministic.
+#include <mutex>
 #include "da_internal.h"
+
+// Scratch of the entry point that allocates nothing (da_select_blocks_global_static): one copy per device, held from
+// the moment the library's code is loaded on a device until the process ends.  Host code never uses this name as an
+// address: static_scratch() asks the runtime for the device address, once per device.
+static __device__ __align__(256) unsigned char scratch[DA_STATIC_SCRATCH_BYTES];
 
 namespace da {
 namespace {
@@ -355,6 +361,27 @@ size_t select_global_workspace(const Geo& q) {
   const size_t bh = (size_t)q.B * q.H, rows = bh * (size_t)q.g, W = ((size_t)q.g + 63) / 64;
   return 256 + up256(bh * 3 * kBins * sizeof(unsigned) + bh * sizeof(SelState)) + 3 * up256(rows * sizeof(int32_t)) +
          2 * up256(rows * W * sizeof(unsigned long long));
+}
+
+// Device address of `scratch` on the current device (looked up on the first call on each device).
+hipError_t static_scratch(void** ptr) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex lock;
+  static void* known[kMaxDevices] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> hold(lock);
+  if (!known[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    known[dev] = p;
+  }
+  *ptr = known[dev];
+  return hipSuccess;
 }
 
 hipError_t launch_select_global(const Geo& q, long long budget, long long cap, const float* scores, int32_t* row_ptr,
