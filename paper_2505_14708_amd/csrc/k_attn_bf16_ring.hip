@@ -51,6 +51,10 @@
 // global memory (L2) straight into registers, only by the waves that need them, while the
 // exponentials are being computed.
 //
+// The normaliser of a row is the sum of its probabilities as the second product sees them, i.e. after their
+// rounding to bf16 (v_dot2c_f32_bf16 with a pair of ones: one instruction per two probabilities): numerator and
+// denominator then carry the same rounding, and a row dominated by one key returns that key's V row exactly.
+//
 // The running max only moves (and O is rescaled) when a row max exceeds it by more than 2^8 in
 // the exponent's units; until then probabilities are formed against the stale max, which is
 // exact after the final division because numerator and denominator share it.
@@ -150,14 +154,14 @@ __device__ __forceinline__ float sum_across_halves(float x) {
 
 // exp / sum / pack of 16 scores (one accumulator tile) into two P operands
 __device__ __forceinline__ void exp_pack(const f32x16& s, float mc, float& lsum, bf16x8& p_lo, bf16x8& p_hi) {
+  const bf16x2 kOnes = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
   for (int i = 0; i < 16; i += 2) {
     float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], kC2, -mc));
     float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i + 1], kC2, -mc));
-    lsum += p0;
-    lsum += p1;
     f32x2 pp = {p0, p1};
     bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+    lsum = __builtin_amdgcn_fdot2_f32_bf16(pb, kOnes, lsum, false);   // the sum of what the second product sees
     if (i < 8) {
       p_lo[i] = pb[0];
       p_lo[i + 1] = pb[1];

@@ -7,6 +7,13 @@ namespace da {
 
 typedef uint4 chunk16;  // 16 bytes
 
+// a source chunk is read exactly once by these kernels: non-temporal, so that the stream leaves the L2 to others
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+__device__ inline chunk16 load_once(const chunk16* p) {
+  const u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // perm / inv / valid arrays for callers that want them.
 __global__ void build_perm_kernel(Geo q, int32_t* perm, int32_t* inv, int32_t* valid) {
   long long slot = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -48,12 +55,12 @@ __global__ __launch_bounds__(256) void permute_rows_kernel(Geo q, const chunk16*
       chunk16 val = make_uint4(0, 0, 0, 0);
       if (s < nv) {
         int u = s / b.vw, v = s - u * b.vw;
-        val = X[far0 + ((long long)u * pitch + v) * far_sn + c];
+        val = load_once(&X[far0 + ((long long)u * pitch + v) * far_sn + c]);
       }
       Y[near0 + (long long)s * cpr + c] = val;
     } else {
       int u = s / b.vw, v = s - u * b.vw;
-      Y[far0 + ((long long)u * pitch + v) * far_sn + c] = X[near0 + (long long)s * cpr + c];
+      Y[far0 + ((long long)u * pitch + v) * far_sn + c] = load_once(&X[near0 + (long long)s * cpr + c]);
     }
   }
 }
@@ -81,7 +88,7 @@ __global__ __launch_bounds__(256) void permute_vt_kernel(Geo q, const E* __restr
     chunk16 val = make_uint4(0, 0, 0, 0);
     if (s < nv) {
       int u = s / b.vw, v = s - u * b.vw;
-      val = Xc[((long long)u * pitch + v) * sn + c];
+      val = load_once(&Xc[((long long)u * pitch + v) * sn + c]);
     }
     *(chunk16*)(tile + s * ld + c * PER) = val;
   }

