@@ -83,10 +83,15 @@ __global__ __launch_bounds__(64) void select_reg_kernel(const float* __restrict_
   const int lane = threadIdx.x;
   const float* in = scores + row * g;
   unsigned key[KPL];
+  {
+    // every load of the row is asked for before the first is used (a column past the end reads the row's last one
+    // instead, so that no load sits behind a branch)
+    float x[KPL];
 #pragma unroll
-  for (int i = 0; i < KPL; ++i) {
-    const int j = lane + 64 * i;
-    key[i] = j < g ? order_key(in[j]) : 0u;           // a column past the end never counts: every trial value is > 0
+    for (int i = 0; i < KPL; ++i) x[i] = in[min(lane + 64 * i, g - 1)];
+#pragma unroll
+    for (int i = 0; i < KPL; ++i)
+      key[i] = lane + 64 * i < g ? order_key(x[i]) : 0u;   // a column past the end never counts: every trial value is > 0
   }
   unsigned thr = 0u;
   bool cut = false;                                   // exactly k keys are >= thr: no tie to resolve, no bit left to find
