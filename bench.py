@@ -49,7 +49,8 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 # rocprofv3) but copied from a counter run of this program: FETCH_SIZE and WRITE_SIZE, scaled by what the same
 # counters read for the row-copy kernel of known size in the same run.  The file named holds the figures and the
 # command; it is regenerated whenever the kernel changes.  Workloads without a counter run: null.
-ATTN_TRAFFIC = {"720p_hunyuan": {"read": 56.36e9, "written": 0.754e9, "source": "profiles/pmc_traffic_720p_hunyuan.txt"}}
+ATTN_TRAFFIC = {"720p_hunyuan": {"read": 56.40e9, "written": 0.744e9, "no_drop_read": 109.89e9, "no_drop_written": 0.731e9,
+                                 "source": "profiles/pmc_attn_720p_hunyuan.txt"}}
 FLOP_PER_MFMA = 2.0 * 32 * 32 * 16     # v_mfma_f32_32x32x16_bf16
 
 
@@ -262,6 +263,8 @@ def main():
     roof["traffic_unit"] = "HBM-side bytes per launch (read + written)"
     roof["traffic_source"] = (tr["source"] + " (a counter run of this program; not measured in this run)") if tr else None
     roof["compulsory_bytes"] = 4.0 * dims.n_pad * w.d * esz * w.B * w.H
+    if tr and "no_drop" in roof:
+        roof["no_drop"]["traffic"] = tr["no_drop_read"] + tr["no_drop_written"]
 
     # ---- what this machine sustains: a pure matrix-instruction loop (~10 ms of it), a plain copy, a plain read
     hbm = {"reorder_qkv_GBs": reorder_bytes / (stage_ms["reorder_qkv"] * 1e-3) / 1e9,
