@@ -117,7 +117,7 @@ int da_build_perm(const da_problem* p, int32_t* perm, int32_t* inv, int32_t* val
  *       summed in slot order (acc = acc + x, one rounding per add) and divided once by
  *       the valid count (DA_POOL_MAX: their maximum instead, exact);
  *   logits [B,H,g,g] float : Q~ K~^T / sqrt(d) in float32 with the fixed order
- *       acc = acc + (q[c]*k[c]) for c = 0..d-1 (multiply and add rounded separately),
+ *       acc = fma(q[c], k[c], acc) for c = 0..d-1 (IEEE fused multiply-add, one rounding per term),
  *       then one multiply by float(1/sqrt(d));
  *   draft  [B,H,g,g] float : row softmax of logits (the draft attention map).
  * q_pool and k_pool are required; logits and draft may each be NULL (then not produced).

@@ -47,7 +47,9 @@ Readings taken where the paper is silent or loose (each is listed in the design 
 Float32 "canonical" variants exist because the kept-block decision is an integer taken
 from floating point: the HIP path and the oracle both evaluate the draft logits in
 float32 with one fixed order of operations (documented at each function), so the
-decision can be compared bit for bit.  Everything else is float64.
+decision can be compared bit for bit.  Everything else is float64, and everything is NumPy
+except the chain of fused multiply-adds of the canonical logits, which is the plain C loop in
+draft_logits_fma.c (built on first use by build_native()).
 """
 from __future__ import annotations
 
@@ -203,18 +205,47 @@ def draft_logits_f64(qp64, kp64):
     return (qp64 @ kp64.T) / math.sqrt(d)
 
 
+_NATIVE = None
+
+
+def build_native(force=False):
+    """Compile the oracle's one C routine (draft_logits_fma.c, beside this file) into oracle/_build/ and return
+    the path of the shared object.  The routine is a plain triple loop around fmaf(); it is in C because an exact
+    fused multiply-add cannot be written with NumPy's float32 operations."""
+    import os
+    import subprocess
+    here = os.path.dirname(os.path.abspath(__file__))
+    src = os.path.join(here, "draft_logits_fma.c")
+    out_dir = os.path.join(here, "_build")
+    lib = os.path.join(out_dir, "libdraftoracle.so")
+    if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(src):
+        os.makedirs(out_dir, exist_ok=True)
+        subprocess.run(["gcc", "-O2", "-ffp-contract=off", "-shared", "-fPIC", src, "-o", lib, "-lm"], check=True)
+    return lib
+
+
+def _native():
+    global _NATIVE
+    if _NATIVE is None:
+        import ctypes
+        L = ctypes.CDLL(build_native())
+        L.da_oracle_draft_logits_fma.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_long] * 3 + [ctypes.c_float]
+        L.da_oracle_draft_logits_fma.restype = None
+        _NATIVE = L
+    return _NATIVE
+
+
 def draft_logits_canonical_f32(qp32, kp32):
     """Float32 draft logits with a fixed order: acc = 0; for c = 0 .. d-1:
-    acc = fl32(acc + fl32(q[c] * k[c])) (multiply and add rounded separately);
-    L = fl32(acc * fl32(1/sqrt(d)))."""
+    acc = fma(q[c], k[c], acc) (IEEE fused multiply-add: the exact product plus acc, rounded once);
+    L = fl32(acc * fl32(1/sqrt(d))).  Evaluated by the C routine in draft_logits_fma.c."""
+    qp32 = np.ascontiguousarray(qp32, dtype=np.float32)
+    kp32 = np.ascontiguousarray(kp32, dtype=np.float32)
     g, d = qp32.shape
-    acc = np.zeros((g, kp32.shape[0]), dtype=np.float32)
-    tmp = np.empty_like(acc)
-    for c in range(d):
-        np.multiply(qp32[:, c:c + 1], kp32[None, :, c], out=tmp)
-        np.add(acc, tmp, out=acc)
+    out = np.empty((g, kp32.shape[0]), dtype=np.float32)
     scale = np.float32(1.0 / math.sqrt(d))
-    return acc * scale
+    _native().da_oracle_draft_logits_fma(qp32.ctypes.data, kp32.ctypes.data, out.ctypes.data, g, kp32.shape[0], d, scale)
+    return out
 
 
 def softmax_rows(L):

@@ -1,16 +1,16 @@
 // Draft logits L = Q~ K~^T / sqrt(d) and the draft attention map softmax(L) (Definition 3.2).
 //
 // The kept-block decision is taken from these logits, so they are evaluated in float32 with
-// one fixed order that a CPU can repeat bit for bit: acc = acc + (q[c]*k[c]) for c ascending,
-// the multiply and the add rounded separately (no fused multiply-add, no matrix cores, no
+// one fixed order that a CPU can repeat bit for bit: acc = fma(q[c], k[c], acc) for c ascending
+// (the IEEE fused multiply-add: one instruction and one rounding per term; no matrix cores, no
 // split sums), then one multiply by float(1/sqrt(d)).  The work is a register-tiled product
 // on the vector ALUs: a workgroup owns a 128x128 tile of L, a thread an 8x8 piece; Q~ and K~
 // pieces go through LDS transposed so a thread reads its 8 rows / 8 columns as 16-byte loads.
 #include <math.h>
 #include "da_internal.h"
 
-// No fused multiply-add anywhere in this file: the pragma covers the code below, and the build
-// also passes -ffp-contract=off for this file.
+// The compiler contracts nothing in this file (the pragma covers the code below, and the build also
+// passes -ffp-contract=off for it): the only fused multiply-adds are the ones written out.
 #pragma clang fp contract(off)
 
 namespace da {
@@ -35,21 +35,33 @@ __global__ __launch_bounds__(256) void draft_logits_kernel(Geo q, const float* _
 #pragma unroll
     for (int b = 0; b < 8; ++b) acc[a][b] = 0.f;
 
-  // loader: thread -> (row r = tid/2, half of the TC channels)
+  // loader: thread -> (row r = tid/2, half of the TC channels), as 16-byte loads (d is a multiple of 4).  The next
+  // stage's loads are asked for before the current stage is multiplied.
   const int lr = tid >> 1, lc = (tid & 1) * (TC / 2);
-  for (int c0 = 0; c0 < q.d; c0 += TC) {
-    {
-      int gr = row0 + lr, gc = col0 + lr;
+  const int gr = row0 + lr, gc = col0 + lr;
+  const float* qrow = qb + (long long)min(gr, q.g - 1) * q.d;
+  const float* krow = kb + (long long)min(gc, q.g - 1) * q.d;
+  float4 nq[2], nk[2];
+  auto fetch = [&](int c0) {
 #pragma unroll
-      for (int j = 0; j < TC / 2; ++j) {
-        int c = c0 + lc + j;
-        float qv = (gr < q.g && c < q.d) ? qb[(long long)gr * q.d + c] : 0.f;
-        float kv = (gc < q.g && c < q.d) ? kb[(long long)gc * q.d + c] : 0.f;
-        qs[lc + j][lr] = qv;
-        ks[lc + j][lr] = kv;
-      }
+    for (int v = 0; v < 2; ++v) {
+      const int c = c0 + lc + 4 * v;
+      const bool in = c < q.d;                          // (a group of four is inside the row or outside it as a whole)
+      nq[v] = in && gr < q.g ? *(const float4*)(qrow + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+      nk[v] = in && gc < q.g ? *(const float4*)(krow + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  };
+  fetch(0);
+  for (int c0 = 0; c0 < q.d; c0 += TC) {
+#pragma unroll
+    for (int v = 0; v < 2; ++v) {
+      qs[lc + 4 * v + 0][lr] = nq[v].x; qs[lc + 4 * v + 1][lr] = nq[v].y;
+      qs[lc + 4 * v + 2][lr] = nq[v].z; qs[lc + 4 * v + 3][lr] = nq[v].w;
+      ks[lc + 4 * v + 0][lr] = nk[v].x; ks[lc + 4 * v + 1][lr] = nk[v].y;
+      ks[lc + 4 * v + 2][lr] = nk[v].z; ks[lc + 4 * v + 3][lr] = nk[v].w;
     }
     __syncthreads();
+    if (c0 + TC < q.d) fetch(c0 + TC);
     const int cend = min(TC, q.d - c0);
     for (int c = 0; c < cend; ++c) {
       float a[8], b[8];
@@ -61,22 +73,31 @@ __global__ __launch_bounds__(256) void draft_logits_kernel(Geo q, const float* _
 #pragma unroll
       for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          float prod = a[i] * b[j];      // rounded on its own: this file is compiled with contraction off
-          acc[i][j] = acc[i][j] + prod;
-        }
+        for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_fmaf(a[i], b[j], acc[i][j]);
     }
     __syncthreads();
   }
   float* out = logits + bh * (long long)q.g * q.g;
+  // a thread's columns come in two runs of four: with g a multiple of 4 a run is inside the row or outside it as a
+  // whole, and 16-byte aligned, so it goes out as one store
+  const bool vec = (q.g & 3) == 0;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     int r = row0 + (i < 4 ? ty * 4 + i : 64 + ty * 4 + (i - 4));
     if (r >= q.g) continue;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      int c = col0 + (j < 4 ? tx * 4 + j : 64 + tx * 4 + (j - 4));
-      if (c < q.g) out[(long long)r * q.g + c] = acc[i][j] * scale;
+    for (int h = 0; h < 2; ++h) {
+      const int c = col0 + 64 * h + tx * 4;
+      float* dst = out + (long long)r * q.g + c;
+      if (vec) {
+        if (c < q.g)
+          *(float4*)dst = make_float4(acc[i][4 * h] * scale, acc[i][4 * h + 1] * scale, acc[i][4 * h + 2] * scale,
+                                      acc[i][4 * h + 3] * scale);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (c + j < q.g) dst[j] = acc[i][4 * h + j] * scale;
+      }
     }
   }
 }

@@ -201,21 +201,62 @@ def test_draft_logits_planted():
                           ref.astype(np.float32))
 
 
-def test_draft_logits_canonical_close_to_f64_and_not_fused():
+def _f32_of_fraction(x):
+    """The float32 nearest to an exact rational (ties to even), normal range; by integer arithmetic only."""
+    from fractions import Fraction
+    if x == 0:
+        return np.float32(0.0)
+    sign = -1 if x < 0 else 1
+    x = abs(Fraction(x))
+    e = x.numerator.bit_length() - x.denominator.bit_length()       # 2^(e-1) <= x < 2^(e+1)
+    if Fraction(2) ** e > x:
+        e -= 1                                                       # now 2^e <= x < 2^(e+1)
+    ulp = Fraction(2) ** (e - 23)
+    n, rem = divmod(x, ulp)
+    n = int(n)
+    if rem * 2 > ulp or (rem * 2 == ulp and n % 2 == 1):
+        n += 1
+    return np.float32(sign * n * float(ulp))                         # n <= 2^24 and ulp a power of two: exact
+
+
+def test_draft_logits_canonical_is_a_chain_of_fused_multiply_adds():
+    """The canonical float32 logits against exact rational arithmetic: every step is the exact product plus the
+    running sum, rounded once to float32; then one multiply by float32(1/sqrt(d)), rounded once."""
+    from fractions import Fraction
     r = _rng(4)
-    qp = r.normal(size=(40, 128)).astype(np.float32)
-    kp = r.normal(size=(50, 128)).astype(np.float32)
+    qp = r.normal(size=(6, 128)).astype(np.float32)
+    kp = r.normal(size=(5, 128)).astype(np.float32)
+    qp[1] *= 1e-3; kp[2] *= 1e3; qp[3, ::2] *= -1            # mixed magnitudes and cancellation
     L32 = oa.draft_logits_canonical_f32(qp, kp)
     L64 = oa.draft_logits_f64(qp.astype(np.float64), kp.astype(np.float64))
-    assert np.abs(L32 - L64).max() < 2e-5
-    # scalar re-evaluation of the stated order for a few entries
+    assert np.abs(L32 - L64).max() < 2e-5 * max(1.0, np.abs(L64).max())
     scale = np.float32(1.0 / math.sqrt(128))
     assert scale.view(np.uint32) == 0x3DB504F3
-    for (i, j) in [(0, 0), (7, 31), (39, 49)]:
-        acc = np.float32(0)
-        for c in range(128):
-            acc = np.float32(acc + np.float32(qp[i, c] * kp[j, c]))
-        assert L32[i, j] == np.float32(acc * scale)
+    for i in range(6):
+        for j in range(5):
+            acc = np.float32(0)
+            for c in range(128):
+                acc = _f32_of_fraction(Fraction(float(qp[i, c])) * Fraction(float(kp[j, c])) + Fraction(float(acc)))
+            want = _f32_of_fraction(Fraction(float(acc)) * Fraction(float(scale)))
+            assert L32[i, j].view(np.uint32) == want.view(np.uint32), (i, j)
+
+
+def test_draft_logits_canonical_fused_not_separate_and_in_channel_order():
+    """Two planted rows tell the fused chain from its look-alikes.  (1) channel 0 leaves acc = -(1 + 2^-11); channel
+    1 multiplies (1 + 2^-12) by itself = 1 + 2^-11 + 2^-24: fused, the 2^-24 survives; with the product rounded first
+    it is lost and the sum is 0.  (2) 2^24 + 1 - 2^24 in channel order is 0 (the 1 is absorbed), in any other order 1."""
+    d = 4
+    a = np.float32(1 + 2.0 ** -12)
+    qp = np.array([[-(1 + 2.0 ** -11), a, 0, 0], [2.0 ** 24, 1.0, -(2.0 ** 24), 0]], dtype=np.float32)
+    kp = np.array([[1.0, a, 0, 0], [1.0, 1.0, 1.0, 0]], dtype=np.float32)
+    L = oa.draft_logits_canonical_f32(qp, kp)
+    assert L[0, 0] == np.float32(2.0 ** -24 * 0.5)          # scale = 1/sqrt(4)
+    assert L[1, 1] == np.float32(0.0)
+    # the test's own rounding helper, on values it must get right
+    from fractions import Fraction
+    assert _f32_of_fraction(Fraction(1) + Fraction(1, 2 ** 24)) == np.float32(1.0)                 # tie: to even
+    assert _f32_of_fraction(Fraction(1) + Fraction(3, 2 ** 24)) == np.float32(1 + 2.0 ** -22)      # tie: to even, upwards
+    assert _f32_of_fraction(Fraction(-5, 3)) == np.float32(-5.0 / 3.0)
 
 
 def test_draft_map_rows_sum_to_one_and_uniform_case():
