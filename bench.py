@@ -109,6 +109,9 @@ def main():
     ap.add_argument("--selection", default="rows", choices=["rows", "whole_map"],
                     help="rows: k key blocks per query block (the headline); whole_map: the threshold over a head's "
                          "whole map (Section 3.2.2), lists of any length")
+    ap.add_argument("--sparsity", type=float, default=None,
+                    help="another sparsity for the chosen workload's shape (0: a dense layer, every block kept)")
+    ap.add_argument("--heads", type=int, default=None, help="another number of heads for the chosen workload's shape")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probes", action="store_true", help="skip the machine's measuring sticks")
     args = ap.parse_args()
@@ -118,6 +121,10 @@ def main():
         sys.exit(2)
 
     w = W.CONFIGS[args.config] if args.config in W.CONFIGS else W.EXTRA_CONFIGS[args.config]
+    if args.sparsity is not None or args.heads is not None:   # a variant of the workload: named so, not the headline
+        s_new = w.sparsity if args.sparsity is None else args.sparsity
+        h_new = w.H if args.heads is None else args.heads
+        w = w.with_(name=f"{w.name}_H{h_new}_s{s_new:g}", sparsity=s_new, H=h_new)
     t0 = time.time()
     Q, K, V = W.make_qkv(w, threads=8)
     print(f"[bench] inputs for {w.name} generated in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)

@@ -192,6 +192,10 @@ int da_wait_failures(uint64_t* count /* host */);
  * are fewer: K is reordered by the pooling pass, and for bf16 Q and O are never copied (the
  * attention kernel reads query rows from, and writes output rows to, their places in the original
  * order, which is Algorithm 1 for Q and Algorithm 2 for O done by addressing).
+ * With every block kept (k = g: sparsity 0, the setting of the denoising steps that Section 4.1 leaves dense)
+ * nothing is ranked: pooling, draft logits and selection are left out, the lists are 0 .. g-1, and the result is
+ * full attention (Definition 3.1).  The same holds for da_forward_ex, and for da_forward_global with a budget of
+ * g*g entries.
  */
 int da_forward(const da_problem* p, const void* Q, const void* K, const void* V, void* O,
                int32_t* idx_out, void* ws, size_t ws_bytes, void* stream);

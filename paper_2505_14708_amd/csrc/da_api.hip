@@ -294,14 +294,24 @@ static int forward_impl(const da_problem* p, bool whole_map, const da_layout* in
   const bool k_in_place = bf16 && q.reordered && q.in.sn == q.d && q.in.sh == q.n_pad * q.d &&
                           q.in.sb == (long long)q.H * q.n_pad * q.d;
   if (k_in_place) kp = const_cast<void*>(K);
-  if ((e = launch_pool_reorder(q, Q, K, q_pool, k_pool, bf16 ? nullptr : qp, k_in_place ? nullptr : kp, s)) != hipSuccess)
-    return DA_ERR_HIP;
-  if ((e = launch_draft_logits(q, q_pool, k_pool, logits, s)) != hipSuccess) return DA_ERR_HIP;
-  // guided sparsity: k per row, or the threshold over the whole map (Section 3.2.2)
-  if (whole_map)
-    e = launch_select_global(q, budget, cap, logits, row_ptr, idx, nullptr, base + w.select, s);
-  else
-    e = launch_select(q, logits, idx, nullptr, s);
+  // Every block kept (sparsity 0, as in the steps Section 4.1 leaves dense): there is nothing to rank.  The lists are
+  // 0 .. g-1 whatever the draft map says, so pooling, logits and selection are left out and only Algorithm 1 runs.
+  const bool all_kept = whole_map ? budget == (long long)q.g * q.g : q.k == q.g;
+  if (all_kept) {
+    if (!k_in_place && (e = launch_permute(q, K, kp, DA_REORDER_ROWS, s)) != hipSuccess) return DA_ERR_HIP;
+    if (!bf16 && (e = launch_permute(q, Q, qp, DA_REORDER_ROWS, s)) != hipSuccess) return DA_ERR_HIP;
+    e = launch_all_lists(q, idx, row_ptr, whole_map ? cap : (long long)q.g * q.g, s);
+  } else {
+    if ((e = launch_pool_reorder(q, Q, K, q_pool, k_pool, bf16 ? nullptr : qp, k_in_place ? nullptr : kp, s)) !=
+        hipSuccess)
+      return DA_ERR_HIP;
+    if ((e = launch_draft_logits(q, q_pool, k_pool, logits, s)) != hipSuccess) return DA_ERR_HIP;
+    // guided sparsity: k per row, or the threshold over the whole map (Section 3.2.2)
+    if (whole_map)
+      e = launch_select_global(q, budget, cap, logits, row_ptr, idx, nullptr, base + w.select, s);
+    else
+      e = launch_select(q, logits, idx, nullptr, s);
+  }
   if (e != hipSuccess) return DA_ERR_HIP;
   // Algorithm 1: reorder V (block-transposed; for bf16 as matrix operands)
   if ((e = launch_permute(q, V, vt, bf16 ? DA_REORDER_VOP : DA_REORDER_VT, s)) != hipSuccess) return DA_ERR_HIP;

@@ -135,6 +135,23 @@ __global__ __launch_bounds__(64) void select_reg_kernel(const float* __restrict_
   }
 }
 
+// Every block kept (k = g, or a whole-map budget of g*g entries): the lists are 0 .. g-1 whatever the scores are.
+// idx: per head g rows of g columns, heads `head_stride` entries apart; row_ptr (optional): [B*H, g+1] offsets i*g.
+__global__ __launch_bounds__(256) void all_lists_kernel(int32_t* __restrict__ idx, int32_t* __restrict__ row_ptr, int g,
+                                                        long long head_stride) {
+  const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long bh = blockIdx.y;
+  if (e < (long long)g * g) idx[bh * head_stride + e] = (int32_t)(e % g);
+  if (row_ptr && e <= g) row_ptr[bh * (g + 1) + e] = (int32_t)(e * g);
+}
+
+hipError_t launch_all_lists(const Geo& q, int32_t* idx, int32_t* row_ptr, long long head_stride, hipStream_t s) {
+  const long long per_head = (long long)q.g * q.g;
+  dim3 grid((unsigned)((per_head + 256) / 256), (unsigned)(q.B * q.H));   // (+256: entry g*g itself is row_ptr's last)
+  hipLaunchKernelGGL(all_lists_kernel, grid, dim3(256), 0, s, idx, row_ptr, q.g, head_stride);
+  return hipGetLastError();
+}
+
 hipError_t launch_select(const Geo& q, const float* scores, int32_t* idx, uint8_t* mask, hipStream_t s) {
   long long rows = (long long)q.B * q.H * q.g;
   size_t lds = (size_t)q.g * sizeof(unsigned);

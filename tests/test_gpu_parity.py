@@ -577,6 +577,62 @@ def test_forward_keep_one_block(torch_mod, cases):
 
 
 
+@pytest.mark.parametrize("name", ["tiny_fp32", "bf16_480p_T3", "f32_ragged", "bf16_B2_T5", "bf16_8x16_ragged"])
+def test_forward_every_block_kept(torch_mod, cases, name):
+    """Sparsity 0: nothing is ranked (the draft stages are left out), every list is 0 .. g-1 and the output is full
+    attention (Definition 3.1) on the original tensors.  Per-row and whole-map entry points, and tensors already in
+    Algorithm 1's order (where K is used in place)."""
+    torch = torch_mod
+    w, Q, K, V, _ = cases[name]
+    say(f"forward, every block kept: {name}")
+    w0 = w.with_(sparsity=0.0)
+    p = da.problem_of(w0)
+    dims = da.da_derive(p)
+    g = dims.g
+    assert dims.k == g
+    as_int = torch.int16 if w.dtype == W.BF16 else torch.int32
+    dQ, dK, dV = (to_dev(x, w.dtype) for x in (Q, K, V))
+    sz = da.da_global_sizes(p)
+    assert sz.budget == g * g
+    ws = torch.empty(max(da.da_workspace_size(p), sz.forward_ws), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xff)                                        # (the logits' place holds NaNs: nobody may read it)
+    O = empty((w.B, w.H, dims.n, w.d), w.dtype)
+    idx = torch.full((w.B, w.H, g, g), -1, dtype=torch.int32, device="cuda")
+    da.da_forward(p, dQ, dK, dV, O, ws, idx)
+    torch.cuda.synchronize()
+    every = np.broadcast_to(np.arange(g, dtype=np.int32), (w.B, w.H, g, g))
+    assert np.array_equal(idx.cpu().numpy(), every)
+    got = to_host_f64(O, w.dtype)
+    tol_max, tol_mean = TOL[w.dtype]
+    for b in range(w.B):
+        for h in range(w.H):
+            q64, k64, v64 = (oa.widen_f64(x[b, h], w.dtype) for x in (Q, K, V))
+            emax, emean = output_error(got[b, h], oa.full_attention(q64, k64, v64))
+            say(f"  {name} head {(b, h)}: max-abs {emax:.3e} mean-abs {emean:.3e}")
+            assert emax <= tol_max and emean <= tol_mean
+    # the whole-map entry point: offsets i*g, the same lists, the same attention
+    O2 = torch.empty_like(O)
+    row_ptr = torch.full((w.B, w.H, g + 1), -1, dtype=torch.int32, device="cuda")
+    cols = torch.full((w.B, w.H, sz.cap), -1, dtype=torch.int32, device="cuda")
+    da.da_forward_global(p, dQ, dK, dV, O2, ws, row_ptr, cols)
+    torch.cuda.synchronize()
+    assert np.array_equal(row_ptr.cpu().numpy(), np.broadcast_to(np.arange(g + 1, dtype=np.int32) * g, (w.B, w.H, g + 1)))
+    assert np.array_equal(cols.cpu().numpy()[:, :, :g * g].reshape(w.B, w.H, g, g), every)
+    assert (cols[:, :, g * g:] == -1).all()
+    emax, emean = output_error(to_host_f64(O2, w.dtype), got)
+    assert emax <= tol_max and emean <= tol_mean          # (two kernels' instantiations: not the same bits)
+    # tensors in Algorithm 1's order
+    Qp, Kp, Vp = (empty((w.B, w.H, dims.n_pad, w.d), w.dtype) for _ in range(3))
+    for x, xp in ((dQ, Qp), (dK, Kp), (dV, Vp)):
+        da.da_permute(p, x, xp, da.DA_REORDER_ROWS)
+    Op = empty((w.B, w.H, dims.n_pad, w.d), w.dtype)
+    da.da_forward_ex(p, Qp, Kp, Vp, Op, ws, None, None, 1, None)
+    back = torch.empty_like(O)
+    da.da_permute(p, Op, back, da.DA_RESTORE)
+    torch.cuda.synchronize()
+    assert torch.equal(back.view(as_int), O.view(as_int))
+
+
 # ----------------------------------------------------------------------------- under graph capture
 @pytest.mark.parametrize("name,whole_map", [("bf16_B2_T5", False), ("f32_ragged", False), ("bf16_480p_T3", True)])
 def test_forward_replayed_from_a_graph(torch_mod, cases, name, whole_map):
