@@ -133,6 +133,41 @@ def test_full_config(case, name, q_scale, full_head):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("q_scale", [1.0, 2.0 ** -5], ids=["as_generated", "nothing_dropped"])
+def test_dense_layer_full_size(q_scale):
+    """A dense layer (sparsity 0) at the headline shape, two heads: da_forward ranks nothing, every workgroup walks all
+    1980 key tiles, and the result is full attention (Definition 3.1).  Sampled query tokens of every block class are
+    compared with the oracle's full attention row by row (a row of full attention depends on nothing but its query);
+    the whole output must be finite.  With Q scaled by 2^-5 the drop rule leaves nothing out."""
+    import torch
+    w = W.CONFIGS["720p_hunyuan"].with_(name="720p_hunyuan_dense", H=2, sparsity=0.0)
+    say(f"dense layer: generating {w.H} heads, N={w.N}")
+    Q, K, V = W.make_qkv(w, threads=8)
+    Q = _scaled(Q, q_scale, w.dtype)
+    p = da.problem_of(w)
+    dims = da.da_derive(p)
+    assert dims.k == dims.g
+    ws = torch.empty(da.da_workspace_size(p), dtype=torch.uint8, device="cuda")
+    O = empty((w.B, w.H, dims.n, w.d), w.dtype)
+    O.fill_(float("nan"))
+    failures_before = da.da_wait_failures()
+    da.da_forward(p, *(to_dev(x, w.dtype) for x in (Q, K, V)), O, ws)
+    torch.cuda.synchronize()
+    assert da.da_wait_failures() == failures_before
+    assert bool(torch.isfinite(O).all())
+    tol_max, tol_mean = TOL[w.dtype]
+    for h in range(w.H):
+        ref = HeadRef(w, Q[0, h], K[0, h], V[0, h])
+        blocks = sample_rows(ref, 16, seed=h)
+        tokens = np.concatenate([ref.perm[b * dims.block + np.arange(0, ref.valid[b], 5)] for b in blocks])
+        q64, k64, v64 = (oa.widen_f64(x[0, h], w.dtype) for x in (Q, K, V))
+        want = oa.full_attention(q64[tokens], k64, v64)
+        got = to_host_f64(O[0, h], w.dtype)[tokens]
+        emax, emean = output_error(got, want)
+        say(f"dense layer head {h}: {len(tokens)} query tokens of {len(blocks)} blocks, max-abs {emax:.3e} mean-abs {emean:.3e}")
+        assert emax <= tol_max and emean <= tol_mean
+
+
 @pytest.mark.parametrize("name,heads,check", [("720p_hunyuan", [0, 7, 16, 23], [0, 23]), ("768p_8x16", [3, 20], [20])],
                          ids=["720p_hunyuan", "768p_8x16"])
 def test_full_config_whole_map(name, heads, check):
