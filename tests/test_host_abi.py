@@ -5,6 +5,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 from oracle import draft_attention as oa
@@ -70,6 +71,36 @@ def test_derive_k_rule():
     assert da.da_derive(p).k == 5
     p = da.problem(1, 1, 4, 16, 16, 128, keep_blocks=500)
     assert da.da_derive(p).k == 16
+
+
+def test_derive_k_rule_against_integer_arithmetic():
+    """Sparsities given in whole per cent: k = g - floor(s g) computed in integers is what both the library and the
+    oracle must return, for every g a frame grid can give up to 5000 and beyond (the product s*g in doubles lands a
+    hair under an integer for many of these pairs: that is what the rule's epsilon is for)."""
+    rng = np.random.default_rng(11)
+    gs = list(range(1, 600)) + [int(x) for x in rng.integers(600, 200000, 1500)]
+    for g in gs:
+        # a grid with exactly g blocks: T = g frames of one 8x8 patch
+        for a in (0, 1, 10, 25, 30, 33, 50, 55, 70, 75, 80, 90, 95, 99):
+            want = max(1, g - (a * g) // 100)
+            s = a / 100.0
+            assert oa.derive_dims(g, 8, 8, 8, 8, s)["k"] == want, (g, a)
+            assert da.da_derive(da.problem(1, 1, g, 8, 8, 128, sparsity=s)).k == want, (g, a)
+            if g <= 40000:
+                assert oa.global_budget(g, s) == max(1, g * g - (a * g * g) // 100), (g, a)
+                assert da.da_global_sizes(da.problem(1, 1, g, 8, 8, 128, sparsity=s)).budget == oa.global_budget(g, s)
+
+
+def test_derive_matches_oracle_on_random_problems():
+    rng = np.random.default_rng(12)
+    for _ in range(3000):
+        T, fh, fw = int(rng.integers(1, 70)), int(rng.integers(1, 100)), int(rng.integers(1, 100))
+        ph, pw = int(rng.integers(1, 17)), int(rng.integers(1, 17))
+        s = float(rng.choice([0.0, 0.1, 0.3, 0.5, 0.75, 0.9, 0.99, rng.uniform(0, 0.999)]))
+        keep = int(rng.integers(0, 3)) * int(rng.integers(1, 50))
+        dims = da.da_derive(da.problem(1, 3, T, fh, fw, 64, ph=ph, pw=pw, sparsity=s, keep_blocks=keep))
+        got = dict(gh=dims.gh, gw=dims.gw, g=dims.g, block=dims.block, n=dims.n, n_pad=dims.n_pad, k=dims.k)
+        assert got == oa.derive_dims(T, fh, fw, ph, pw, s, keep), (T, fh, fw, ph, pw, s, keep)
 
 
 def _status(fn, *args):
