@@ -160,6 +160,8 @@ int da_permute(const da_problem* p, const void* X, void* Y, int mode, void* stre
  * bounds the problem: roughly g/2 + 4*min(g, 4k) bytes must fit in 32 KB (g up to about 7000 with
  * nothing dropped, far more when k << g), and g * block / 64 < 2^22; larger problems return DA_ERR_UNSUPPORTED.  Its waits for tiles are
  * bounded; should one ever run out (no valid input makes it), the rows concerned are written as NaN.
+ * Lists that are not what is asked for above (entries outside [0,g), repeats) give unspecified results but no access
+ * outside the arrays: an entry that is no block number is left out.
  */
 int da_sparse_attn(const da_problem* p, const void* Qp, const void* Kp, const void* Vt,
                    const int32_t* idx, void* Op, float* lse, void* stream);
@@ -266,7 +268,9 @@ int da_select_blocks_global_static(const da_problem* p, const float* scores, int
  * cols[(b*H+h)*cap + row_ptr[(b*H+h)*(g+1) + i] .. row_ptr[.. + i + 1]) (entries in [0,g), any order, no repeats;
  * 0 <= row_ptr[..][i] <= row_ptr[..][i+1] <= cap; cap a multiple of 4).  A query block with an empty list gets zero
  * rows.  Everything else as da_sparse_attn (its k is not used; the cut of the bf16 drop rule goes by each row's own
- * number of keys); the bf16 kernel's LDS bound is that of k = g.
+ * number of keys); the bf16 kernel's LDS bound is that of k = g.  Offsets and entries that are not what is asked for
+ * give unspecified results but no access outside the arrays (offsets are brought into [0,cap], entries outside [0,g)
+ * are left out).
  */
 int da_sparse_attn_lists(const da_problem* p, const void* Qp, const void* Kp, const void* Vt, const int32_t* row_ptr,
                          const int32_t* cols, int64_t cap, void* Op, float* lse, void* stream);

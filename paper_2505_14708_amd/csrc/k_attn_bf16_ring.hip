@@ -362,9 +362,11 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   const int32_t* list = idx + qb * k;
   if (LISTS) {
     const int32_t* rp = row_ptr + bh * (g + 1) + (has_block ? my_block : 0);
-    const int begin = rp[0];
+    // (offsets that are not what the interface asks for are brought into the head's stretch: such lists give
+    // unspecified results, but nothing outside the arrays is read)
+    const int begin = min(max(rp[0], 0), (int)cap);
     list = idx + bh * cap + begin;
-    k = rp[1] - begin;
+    k = min(max(rp[1] - begin, 0), (int)cap - begin);
     // the cut of the drop rule goes by the number of keys in this row
     skip = log2f((float)max(k, 1) * (float)BLOCK) + kDropLog2;
   }
@@ -419,12 +421,13 @@ __global__ __launch_bounds__(512, 2) void attn_bf16_ring_kernel(Geo q, const uns
   __syncthreads();
   if (live && lane == 0) atomicOr(&ctrl[28], 1 << wave);   // which waves take tiles at all
   if (lister) {
+    // (an entry that is no block number is left out: it must not reach the bitmap, let alone an address)
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      if (pre[i] >= 0) atomicOr(&bitmap[qblk * bw + (pre[i] >> 5)], 1u << (pre[i] & 31));
+      if ((unsigned)pre[i] < (unsigned)g) atomicOr(&bitmap[qblk * bw + (pre[i] >> 5)], 1u << (pre[i] & 31));
     for (int e = lane + 256; e < k; e += 64) {
       int j = list[e];
-      atomicOr(&bitmap[qblk * bw + (j >> 5)], 1u << (j & 31));
+      if ((unsigned)j < (unsigned)g) atomicOr(&bitmap[qblk * bw + (j >> 5)], 1u << (j & 31));
     }
   }
   __syncthreads();

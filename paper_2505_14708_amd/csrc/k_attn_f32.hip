@@ -38,11 +38,15 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(Geo q, const float* __rest
   int len = q.k;
   if (row_ptr) {
     const int32_t* rp = row_ptr + bh * (q.g + 1) + (qb - bh * q.g);
-    list = idx + bh * cap + rp[0];
-    len = rp[1] - rp[0];
+    // (offsets that are not what the interface asks for are brought into the head's stretch, and an entry that is no
+    // block number is left out: such lists give unspecified results, but nothing outside the arrays is touched)
+    const int begin = min(max(rp[0], 0), (int)cap);
+    list = idx + bh * cap + begin;
+    len = min(max(rp[1] - begin, 0), (int)cap - begin);
   }
   for (int t = 0; t < len; ++t) {
     int j = list[t];
+    if ((unsigned)j >= (unsigned)q.g) continue;          // (the same in every lane)
     int nv = block_valid(q, j);
     const float4* ksrc = (const float4*)(Kp + (bh * q.n_pad + (long long)j * 64) * D);
     const float4* vsrc = (const float4*)(Vt + (bh * q.g + j) * (long long)D * 64);

@@ -633,6 +633,40 @@ def test_forward_every_block_kept(torch_mod, cases, name):
     assert torch.equal(back.view(as_int), O.view(as_int))
 
 
+@pytest.mark.parametrize("name", ["bf16_480p_T3", "f32_ragged", "bf16_8x16_ragged"])
+def test_sparse_attn_survives_lists_that_are_not_lists(torch_mod, cases, name):
+    """Entries that are no block numbers and offsets outside the head's stretch are left out / brought into range by
+    the kernels: the calls run to their end, touch nothing outside the arrays, and a call with proper lists afterwards
+    gives the proper result."""
+    torch = torch_mod
+    w, Q, K, V, refs = cases[name]
+    say(f"malformed lists {name}")
+    idx_np = np.stack([np.stack([refs[(b, h)].idx for h in range(w.H)]) for b in range(w.B)])
+    p, dims, Qp, Kp, Vt, idx_good = _attn_inputs(torch, w, Q, K, V, refs, idx_np)
+    g, k = dims.g, dims.k
+    ref = refs[(0, 0)]
+    Op = empty((w.B, w.H, dims.n_pad, w.d), w.dtype)
+    rng = np.random.default_rng(5)
+    junk = rng.integers(-2 ** 31, 2 ** 31 - 1, size=(w.B, w.H, g, k), dtype=np.int64).astype(np.int32)
+    junk[:, :, ::3] = rng.integers(-3, g + 3, size=junk[:, :, ::3].shape)       # near misses and hits mixed
+    failures = da.da_wait_failures()
+    da.da_sparse_attn(p, Qp, Kp, Vt, torch.from_numpy(junk).cuda(), Op, None)
+    torch.cuda.synchronize()
+    cap = (g * g + g + 3) & ~3
+    rp = rng.integers(-5 * cap, 5 * cap, size=(w.B, w.H, g + 1), dtype=np.int64).astype(np.int32)
+    cols = rng.integers(-2 ** 31, 2 ** 31 - 1, size=(w.B, w.H, cap), dtype=np.int64).astype(np.int32)
+    da.da_sparse_attn_lists(p, Qp, Kp, Vt, torch.from_numpy(rp).cuda(), torch.from_numpy(cols).cuda(), cap, Op, None)
+    torch.cuda.synchronize()
+    assert da.da_wait_failures() == failures
+    da.da_sparse_attn(p, Qp, Kp, Vt, idx_good, Op, None)
+    torch.cuda.synchronize()
+    got = to_host_f64(Op, w.dtype)[0, 0]
+    want = ref.attention()
+    rows = ref.perm >= 0
+    emax, emean = output_error(got[rows], want[rows])
+    assert emax <= TOL[w.dtype][0] and emean <= TOL[w.dtype][1]
+
+
 # ----------------------------------------------------------------------------- under graph capture
 @pytest.mark.parametrize("name,whole_map", [("bf16_B2_T5", False), ("f32_ragged", False), ("bf16_480p_T3", True)])
 def test_forward_replayed_from_a_graph(torch_mod, cases, name, whole_map):
