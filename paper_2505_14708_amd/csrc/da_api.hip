@@ -98,7 +98,7 @@ Workspace plan_workspace(const Geo& q, long long lists_cap = 0) {
   w.op = off; off += direct ? 0 : big;
   w.q_pool = off; off += pooled;
   w.k_pool = off; off += pooled;
-  w.logits = off; off += align_up(bh * (size_t)q.g * q.g * sizeof(float));
+  w.logits = off; off += align_up(bh * (size_t)q.g * q.g * sizeof(float) + kSelectSlack);   // (the selector may read on past a row's end)
   w.idx = off; off += align_up(bh * (lists_cap > 0 ? (size_t)lists_cap : (size_t)q.g * q.k) * sizeof(int32_t));
   w.row_ptr = off; off += lists_cap > 0 ? align_up(bh * ((size_t)q.g + 1) * sizeof(int32_t)) : 0;
   w.select = off; off += lists_cap > 0 ? align_up(select_global_workspace(q)) : 0;
@@ -168,7 +168,7 @@ int da_select_blocks(const da_problem* p, const float* scores, int32_t* idx, uin
   if (st != DA_OK) return st;
   if (!scores || !idx) return DA_ERR_NULL;
   if (misaligned(scores) || misaligned(idx) || misaligned(mask)) return DA_ERR_ALIGN;
-  return hip_status(launch_select(q, scores, idx, mask, (hipStream_t)stream));
+  return hip_status(launch_select(q, scores, idx, mask, false, (hipStream_t)stream));
 }
 
 int da_permute(const da_problem* p, const void* X, void* Y, int mode, void* stream) {
@@ -310,7 +310,7 @@ static int forward_impl(const da_problem* p, bool whole_map, const da_layout* in
     if (whole_map)
       e = launch_select_global(q, budget, cap, logits, row_ptr, idx, nullptr, base + w.select, s);
     else
-      e = launch_select(q, logits, idx, nullptr, s);
+      e = launch_select(q, logits, idx, nullptr, true, s);
   }
   if (e != hipSuccess) return DA_ERR_HIP;
   // Algorithm 1: reorder V (block-transposed; for bf16 as matrix operands)

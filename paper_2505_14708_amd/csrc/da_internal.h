@@ -86,7 +86,10 @@ hipError_t launch_pool_reorder(const Geo& q, const void* Q, const void* K, float
                                void* Kp, hipStream_t s);
 hipError_t launch_draft_logits(const Geo& q, const float* q_pool, const float* k_pool, float* logits, hipStream_t s);
 hipError_t launch_row_softmax(const Geo& q, const float* logits, float* draft, hipStream_t s);
-hipError_t launch_select(const Geo& q, const float* scores, int32_t* idx, uint8_t* mask, hipStream_t s);
+// slack: kSelectSlack bytes behind `scores` may be read (their values are not used); without it the last few rows go
+// through a second launch that stays inside the array
+constexpr size_t kSelectSlack = 64 * 64 * sizeof(float);
+hipError_t launch_select(const Geo& q, const float* scores, int32_t* idx, uint8_t* mask, bool slack, hipStream_t s);
 hipError_t launch_all_lists(const Geo& q, int32_t* idx, int32_t* row_ptr, long long head_stride, hipStream_t s);
 // idx: k columns per row; or, with row_ptr [B,H,g+1], lists of any length, the lists of head bh one after the
 // other from idx + bh * cap on

@@ -76,19 +76,23 @@ __global__ __launch_bounds__(64) void select_kernel(const float* __restrict__ sc
 
 
 // Keys in registers: KPL keys per lane, column of key i of lane l is l + 64 i.
-template <int KPL>
-__global__ __launch_bounds__(64) void select_reg_kernel(const float* __restrict__ scores, int32_t* __restrict__ idx,
+// READ_ON: a column past the end of the row may be read from the rows that follow (the launcher gives this
+// instantiation only rows for which that stays inside the array).
+template <int KPL, bool READ_ON>
+__global__ __launch_bounds__(64, KPL == 64 ? 4 : 1) void select_reg_kernel(const float* __restrict__ scores, int32_t* __restrict__ idx,
                                                         uint8_t* __restrict__ mask, int g, int k) {
   const long long row = blockIdx.x;
   const int lane = threadIdx.x;
   const float* in = scores + row * g;
   unsigned key[KPL];
   {
-    // every load of the row is asked for before the first is used (a column past the end reads the row's last one
-    // instead, so that no load sits behind a branch)
+    // Every load of the row is asked for before the first is used, none behind a branch of its own.  A column past
+    // the end of the row reads on into the rows that follow (what it reads is not used): the addresses are then one
+    // base plus constants, two registers instead of two per load, and twice as many rows fit a SIMD.  The rows so
+    // close to the end of the array that this would leave it read their last column instead.
     float x[KPL];
 #pragma unroll
-    for (int i = 0; i < KPL; ++i) x[i] = in[min(lane + 64 * i, g - 1)];
+    for (int i = 0; i < KPL; ++i) x[i] = READ_ON ? in[lane + 64 * i] : in[min(lane + 64 * i, g - 1)];
 #pragma unroll
     for (int i = 0; i < KPL; ++i)
       key[i] = lane + 64 * i < g ? order_key(x[i]) : 0u;   // a column past the end never counts: every trial value is > 0
@@ -98,8 +102,13 @@ __global__ __launch_bounds__(64) void select_reg_kernel(const float* __restrict_
   for (int bit = 31; bit >= 0; --bit) {
     const unsigned cand = thr | (1u << bit);
     int cnt = 0;
+    // (eight keys at a time: with all the lane masks of a pass alive at once the scalar registers run out)
 #pragma unroll
-    for (int i = 0; i < KPL; ++i) cnt += __popcll(__ballot(key[i] >= cand));
+    for (int i0 = 0; i0 < KPL; i0 += 8) {
+#pragma unroll
+      for (int i = i0; i < i0 + 8; ++i) cnt += __popcll(__ballot(key[i] >= cand));
+      __builtin_amdgcn_sched_barrier(0);
+    }
     if (cnt >= k) thr = cand;
     if (cnt == k) {                                   // (the same in every lane)
       cut = true;
@@ -152,15 +161,30 @@ hipError_t launch_all_lists(const Geo& q, int32_t* idx, int32_t* row_ptr, long l
   return hipGetLastError();
 }
 
-hipError_t launch_select(const Geo& q, const float* scores, int32_t* idx, uint8_t* mask, hipStream_t s) {
+template <int KPL>
+static void launch_select_reg(const Geo& q, long long rows, const float* scores, int32_t* idx, uint8_t* mask, bool slack,
+                              hipStream_t s) {
+  // rows whose 64 * KPL columns starting at the row's first all lie inside the array: all but the last few, or all
+  // of them when the caller vouches for kSelectSlack readable bytes behind the array
+  const long long spill = 64LL * KPL - q.g;           // columns read past the end of a row (>= 0)
+  const long long last = spill > 0 && !slack ? (spill + q.g - 1) / q.g : 0;
+  const long long head = rows > last ? rows - last : 0;
+  if (head > 0)
+    hipLaunchKernelGGL((select_reg_kernel<KPL, true>), dim3((unsigned)head), dim3(64), 0, s, scores, idx, mask, q.g, q.k);
+  if (rows > head)
+    hipLaunchKernelGGL((select_reg_kernel<KPL, false>), dim3((unsigned)(rows - head)), dim3(64), 0, s, scores + head * q.g,
+                       idx + head * q.k, mask ? mask + head * q.g : nullptr, q.g, q.k);
+}
+
+hipError_t launch_select(const Geo& q, const float* scores, int32_t* idx, uint8_t* mask, bool slack, hipStream_t s) {
   long long rows = (long long)q.B * q.H * q.g;
   size_t lds = (size_t)q.g * sizeof(unsigned);
   if (q.g <= 64 * 16)
-    hipLaunchKernelGGL(select_reg_kernel<16>, dim3((unsigned)rows), dim3(64), 0, s, scores, idx, mask, q.g, q.k);
+    launch_select_reg<16>(q, rows, scores, idx, mask, slack, s);
   else if (q.g <= 64 * 32)
-    hipLaunchKernelGGL(select_reg_kernel<32>, dim3((unsigned)rows), dim3(64), 0, s, scores, idx, mask, q.g, q.k);
+    launch_select_reg<32>(q, rows, scores, idx, mask, slack, s);
   else if (q.g <= 64 * 64)
-    hipLaunchKernelGGL(select_reg_kernel<64>, dim3((unsigned)rows), dim3(64), 0, s, scores, idx, mask, q.g, q.k);
+    launch_select_reg<64>(q, rows, scores, idx, mask, slack, s);
   else if (lds <= 64 * 1024)
     hipLaunchKernelGGL(select_kernel<true>, dim3((unsigned)rows), dim3(64), lds, s, scores, idx, mask, q.g, q.k);
   else
