@@ -49,7 +49,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 # rocprofv3) but copied from a counter run of this program: FETCH_SIZE and WRITE_SIZE, scaled by what the same
 # counters read for the row-copy kernel of known size in the same run.  The file named holds the figures and the
 # command; it is regenerated whenever the kernel changes.  Workloads without a counter run: null.
-ATTN_TRAFFIC = {"720p_hunyuan": {"read": 56.40e9, "written": 0.744e9, "no_drop_read": 109.89e9, "no_drop_written": 0.731e9,
+ATTN_TRAFFIC = {"720p_hunyuan": {"read": 56.38e9, "written": 0.744e9, "no_drop_read": 110.27e9, "no_drop_written": 0.731e9,
                                  "source": "profiles/pmc_attn_720p_hunyuan.txt"}}
 FLOP_PER_MFMA = 2.0 * 32 * 32 * 16     # v_mfma_f32_32x32x16_bf16
 
